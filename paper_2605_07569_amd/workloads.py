@@ -1,0 +1,146 @@
+"""Seeded synthetic workloads: shard geometry and N(0,1) inputs shaped like the paper's runs.
+
+This module serves both the HIP library's tests/bench and the CPU oracle's tests.  It holds none of
+the method's arithmetic: only which global token ranges and heads a device owns, which KV chunks
+stream past it (HexiSeq Sec. 3.2: uneven group lengths L_k, per-rank head counts n_d; App. A.4: one
+source KV block per ring step), and seeded random tensors.  The paper trains on tokenised text; the
+attention cost and correctness do not depend on token identity, so N(0,1) tensors stand in for it.
+
+A segment is ``(start, length)`` in global token positions.  A shard (or a chunk) is a list of
+segments in ascending order; its rows are the segments' tokens packed back to back.
+"""
+from dataclasses import dataclass, field, replace
+from typing import List, Optional, Tuple
+
+import torch
+
+K = 1024
+Seg = Tuple[int, int]
+
+TENSOR_IDS = {"q": 0, "k": 1, "v": 2, "d_o": 3, "cuts": 9}
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    dtype: str                      # "bf16" | "f32": element type of q, k, v, dO
+    n_q_heads: int                  # local (assigned) heads
+    n_kv_heads: int
+    head_dim: int
+    l_tot: int                      # global sequence length
+    q_segs: List[Seg]               # this device's query shard
+    chunks: List[List[Seg]]         # KV chunk list in ring order, each a segment list
+    k_scale: float = 1.0            # K is multiplied by this before rounding to dtype
+    kv_of_q: Optional[List[int]] = None  # None: q head h reads kv head h // (nq / nkv)
+    note: str = ""
+
+    @property
+    def lq(self):
+        return sum(n for _, n in self.q_segs)
+
+    @property
+    def scale(self):
+        return 1.0 / float(self.head_dim) ** 0.5
+
+    @property
+    def torch_dtype(self):
+        return torch.bfloat16 if self.dtype == "bf16" else torch.float32
+
+
+def zigzag_segs(rank: int, n_ranks: int, l_tot: int) -> List[Seg]:
+    """Load-balanced causal layout: 2R equal blocks, rank r owns blocks r and 2R-1-r."""
+    blk = l_tot // (2 * n_ranks)
+    assert blk * 2 * n_ranks == l_tot
+    return [(rank * blk, blk), ((2 * n_ranks - 1 - rank) * blk, blk)]
+
+
+def _seeded_cuts(seed: int, lo: int, hi: int, n_parts: int, min_len: int, quantum: int) -> List[int]:
+    """n_parts-1 cut points, multiples of `quantum` strictly inside (lo, hi), every part >= min_len.
+
+    Rejection sampling from a torch CPU generator seeded with (seed, tensor id "cuts")."""
+    g = torch.Generator().manual_seed(seed * 16 + TENSOR_IDS["cuts"])
+    n_slots = (hi - lo) // quantum
+    for _ in range(10000):
+        cuts = sorted((lo + quantum * int(c)) for c in
+                      (torch.randint(1, n_slots, (n_parts - 1,), generator=g)).tolist())
+        edges = [lo] + cuts + [hi]
+        if all(b - a >= min_len for a, b in zip(edges[:-1], edges[1:])):
+            return cuts
+    raise RuntimeError("cut sampling did not converge")
+
+
+def config(idx: int, seed: int = 20260507, shrink: int = 1) -> Workload:
+    """The five shard configurations (idx 1..5).  `shrink` divides every token count (shape-preserving
+    minis for full-tensor oracle comparison); head counts, head_dim and chunk counts are unchanged."""
+    s = shrink
+    if idx == 1:
+        w = Workload("cfg1_tiny_fp32", "f32", 4, 4, 64, 2 * K // s, [(K // s, K // s)],
+                     [[(0, K // s)], [(K // s, K // s)]], note="tokens 1024..2047 of 2048, 2 chunks")
+    elif idx == 2:
+        lt, r = 128 * K // s, 8
+        w = Workload("cfg2_3b_zigzag", "bf16", 24, 8, 128, lt, zigzag_segs(0, r, lt),
+                     [zigzag_segs(j, r, lt) for j in range(r)],
+                     note="128K zigzag CP over 8 shards, rank 0 (blocks 0 and 15), chunk j = rank j's pair")
+    elif idx == 3:
+        lt = 256 * K // s
+        fixed = [20 * K // s, 12 * K // s, 40 * K // s, 24 * K // s]
+        cuts = _seeded_cuts(seed, 96 * K // s, lt, 4, 8 * K // s, K // s)
+        edges = [0, fixed[0], fixed[0] + fixed[1], sum(fixed[:3]), sum(fixed)] + cuts + [lt]
+        shards = [(a, b - a) for a, b in zip(edges[:-1], edges[1:])]
+        w = Workload("cfg3_8b_asym", "bf16", 12, 3, 128, lt, [shards[2]], [[sh] for sh in shards],
+                     note="256K cut into 8 uneven shards; owns the 40K shard at 32K and 12 of 32 q heads")
+    elif idx == 4:
+        lt, r = 512 * K // s, 16
+        w = Workload("cfg4_8b_long", "bf16", 32, 8, 128, lt, zigzag_segs(3, r, lt),
+                     [zigzag_segs(j, r, lt) for j in range(r)], k_scale=3.0,
+                     note="512K zigzag CP over 16 shards, rank 3, K scaled x3")
+    elif idx == 5:
+        lt, c = 1024 * K // s, 32 * K // s
+        w = Workload("cfg5_70b_hp", "bf16", 8, 1, 128, lt, [(480 * K // s, c)],
+                     [[(j * c, c)] for j in range(32)],
+                     note="1M tokens; one HP group (8 q / 1 kv head), 32K query shard at 480K, 32 chunks")
+    else:
+        raise ValueError("config index must be 1..5")
+    if s != 1:
+        w = replace(w, name=w.name + f"_div{s}")
+    return w
+
+
+def contiguous_chunks(w: Workload, n_chunks: int) -> Workload:
+    """Alternative chunking of the same key set: n equal contiguous chunks at offsets j*Lc."""
+    lc = w.l_tot // n_chunks
+    assert lc * n_chunks == w.l_tot
+    return replace(w, name=w.name + "_contig", chunks=[[(j * lc, lc)] for j in range(n_chunks)])
+
+
+def _randn(shape, seed, tensor_id, block_rows=1 << 16):
+    g = torch.Generator().manual_seed(seed * 16 + tensor_id)
+    return torch.randn(shape, generator=g, dtype=torch.float32)
+
+
+def make_inputs(w: Workload, seed: int = 20260507):
+    """q, d_o: [Lq, nq, d]; k, v: [l_tot, nkv, d] in GLOBAL token order -- CPU tensors of w's dtype.
+
+    Each tensor is N(0,1) from its own torch CPU generator seeded by (seed, tensor id), then K is
+    scaled by w.k_scale, then everything is rounded (nearest-even) to the workload dtype."""
+    dt = w.torch_dtype
+    q = _randn((w.lq, w.n_q_heads, w.head_dim), seed, TENSOR_IDS["q"]).to(dt)
+    d_o = _randn((w.lq, w.n_q_heads, w.head_dim), seed, TENSOR_IDS["d_o"]).to(dt)
+    k = _randn((w.l_tot, w.n_kv_heads, w.head_dim), seed, TENSOR_IDS["k"])
+    if w.k_scale != 1.0:
+        k.mul_(w.k_scale)
+    k = k.to(dt)
+    v = _randn((w.l_tot, w.n_kv_heads, w.head_dim), seed, TENSOR_IDS["v"]).to(dt)
+    return dict(q=q, k=k, v=v, d_o=d_o)
+
+
+def gather_rows(x: torch.Tensor, segs: List[Seg]) -> torch.Tensor:
+    """Rows of a global-order tensor for a segment list, packed back to back (a copy)."""
+    if len(segs) == 1:
+        s, n = segs[0]
+        return x[s:s + n].contiguous()
+    return torch.cat([x[s:s + n] for s, n in segs], dim=0).contiguous()
+
+
+def seg_positions(segs: List[Seg]) -> torch.Tensor:
+    return torch.cat([torch.arange(s, s + n, dtype=torch.int64) for s, n in segs])
