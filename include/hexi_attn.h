@@ -1,0 +1,154 @@
+/*
+ * hexi_attn.h -- C ABI of the MI355X (gfx950) chunked-ring causal attention library.
+ *
+ * One device's share of HexiSeq's asymmetric CP-HP attention (Sec. 3.2): a query shard of
+ * arbitrary length and global offset (uneven group lengths L_k, Sec. 4.1), an arbitrary packed
+ * subset of attention heads (per-rank head counts n_d, possibly non-contiguous ranges packed into
+ * contiguous buffers, Sec. 3.2 "Sub-ring KV exchange"), run forward and backward against a stream
+ * of source KV blocks, one per ring step (App. A.4, Eq. 10-12), with forward, backward and
+ * recomputation all counted as attention work (App. A.1).  The paper presupposes ordinary softmax
+ * attention and states no formula for it; the mask, scale, GQA map and log-sum-exp merge below are
+ * the textbook ones.
+ *
+ * Conventions
+ *   - All tensor pointers are DEVICE pointers owned by the caller; descriptors, segment lists and
+ *     kv_of_q are HOST pointers read during the call only.  The library allocates no device memory
+ *     and keeps no state between calls except a thread-local error string.
+ *   - Every device call is enqueued on `hip_stream` (a hipStream_t; NULL = the default stream) and
+ *     returns without synchronising.  On error nothing is enqueued.
+ *   - Return value: HEXI_OK (0) or a negative error code; hexi_last_error() describes it.
+ *   - Causal mask on GLOBAL positions, diagonal inclusive: key j is visible to query row i iff
+ *     pos(j) <= pos(i).  Rows with no visible key in a chunk get lse = -INFINITY and o = 0.
+ *   - LSE values are natural logarithms of the sum of exp(softmax_scale * <q, k>).
+ *   - Layouts: q, d_o: [Lq][n_q_heads][head_dim] with the strides of the descriptor (elements);
+ *     k, v: [Lc][n_kv_heads][head_dim] likewise; the head_dim stride is 1.  fp32 outputs are dense:
+ *     o, dq_acc: [Lq][n_q_heads][head_dim]; dk, dv: [Lc][n_kv_heads][head_dim]; lse, delta:
+ *     [n_q_heads][Lq].  Lq / Lc are the total lengths of q_range / kv_range.
+ */
+#ifndef HEXI_ATTN_H
+#define HEXI_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HEXI_OK            0
+#define HEXI_EINVAL       (-1)  /* null pointer, bad size, unsorted/overlapping/empty segments, bad head map */
+#define HEXI_EUNSUPPORTED (-2)  /* head_dim / dtype combination without a kernel, position >= 2^31-1 */
+#define HEXI_EALIGN       (-3)  /* a tensor base pointer or token/head stride is not 16-byte aligned */
+#define HEXI_EWORKSPACE   (-4)  /* workspace smaller than hexi_workspace_bytes() */
+#define HEXI_EHIP         (-5)  /* the HIP runtime refused a launch */
+
+#define HEXI_BF16 0
+#define HEXI_F32  1
+
+#define HEXI_MAX_SEGS 16
+
+/* flags */
+#define HEXI_ACCUMULATE     1u  /* fwd: merge the chunk's result into o/lse in place (fused LSE merge);
+                                   bwd: dk/dv += instead of = */
+#define HEXI_COMPUTE_DELTA  2u  /* bwd: first fill delta = rowsum(d_o * o) from the merged o */
+
+#define HEXI_TILE_EMPTY   0
+#define HEXI_TILE_FULL    1
+#define HEXI_TILE_PARTIAL 2
+
+/* Global token range [start, start+len). */
+typedef struct { int64_t start, len; } hexi_seg;
+
+/* A shard or a KV chunk: 1..HEXI_MAX_SEGS segments, ascending, non-overlapping, len > 0.  The rows
+ * (columns) of the device tensors are the segments' tokens packed back to back in this order.  One
+ * segment = a contiguous shard; two = a zigzag pair. */
+typedef struct { int32_t n_segs; const hexi_seg* segs; } hexi_range;
+
+typedef struct {
+    int32_t dtype;              /* HEXI_BF16 | HEXI_F32: element type of q, k, v, d_o */
+    int32_t head_dim;           /* 128 (bf16); 64 or 128 (f32) */
+    int32_t n_q_heads;          /* local (assigned) q heads, packed */
+    int32_t n_kv_heads;         /* local kv heads, packed */
+    const int32_t* kv_of_q;     /* HOST [n_q_heads]: local kv head read by each local q head;
+                                   NULL => h / (n_q_heads / n_kv_heads) */
+    float   softmax_scale;      /* e.g. 1/sqrt(head_dim) */
+    int64_t q_stride_tok, q_stride_head;    /* strides of q and d_o, in elements */
+    int64_t kv_stride_tok, kv_stride_head;  /* strides of k and v, in elements */
+} hexi_attn_desc;
+
+/*
+ * Offset / mask bookkeeping for one (query shard, KV chunk) pair -- the integer side of the uneven
+ * shard lengths of Sec. 3.2 / Sec. 4.1 and of the per-step source block of App. A.4.  Pure host
+ * function, exact integer arithmetic, no GPU needed.  Any output pointer may be NULL.
+ *   q_pos [Lq], kv_pos [Lc]: global position of every packed row / column (HOST, int32).
+ *   tile_class: HOST uint8, row-major [ceil(Lq/tile_m)][ceil(Lc/tile_n)], HEXI_TILE_* per tile
+ *               (tiles clipped at the ragged edge): EMPTY = no visible pair, FULL = all visible.
+ *   n_pairs: number of visible (row, column) pairs of the whole grid.
+ * Errors: HEXI_EINVAL for malformed ranges or tile sizes <= 0; HEXI_EUNSUPPORTED if a position
+ * does not fit int32.
+ */
+int hexi_shard_mask(const hexi_range* q_range, const hexi_range* kv_range, int32_t tile_m, int32_t tile_n,
+                    int32_t* q_pos, int32_t* kv_pos, uint8_t* tile_class, int64_t* n_pairs);
+
+/*
+ * One ring step forward (App. A.4, Eq. 11: the local query block against one source KV block):
+ * for every local q head h and shard row i, over the chunk's visible columns j,
+ *   s_ij = softmax_scale * <q_ih, k_j,kv(h)>,  lse_ih = ln sum_j exp(s_ij),
+ *   o_ih = sum_j exp(s_ij - lse_ih) * v_j,kv(h)      (normalised partial result).
+ * Without HEXI_ACCUMULATE o/lse are overwritten with this chunk's partial; with it they are the
+ * running accumulators and the partial is merged in place by the rule of hexi_attn_merge_lse (start
+ * from o = 0, lse = -INFINITY).  A chunk wholly in the shard's future costs one fill (or nothing
+ * under HEXI_ACCUMULATE).  o: fp32 [Lq][nq][d]; lse: fp32 [nq][Lq].  workspace may be NULL when
+ * hexi_workspace_bytes() is 0.
+ */
+int hexi_attn_fwd_chunk(const hexi_attn_desc* desc, const hexi_range* q_range, const hexi_range* kv_range,
+                        const void* q, const void* k, const void* v,
+                        float* o, float* lse, uint32_t flags,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Combine two normalised partial results over disjoint key sets (the rule that makes the ring's
+ * per-step results equal un-sharded attention, Sec. 3.2 "preserving attention semantics"):
+ *   lse = ln(e^lse_acc + e^lse_part);  o = e^(lse_acc - lse) o_acc + e^(lse_part - lse) o_part,
+ * written back into o_acc / lse_acc.  -INFINITY is the identity.  If o_final is not NULL the merged
+ * o is also written there in o_final_dtype (HEXI_BF16 or HEXI_F32), dense [n_rows][nq][d].
+ * o_*: fp32 [n_rows][n_q_heads][head_dim]; lse_*: fp32 [n_q_heads][n_rows].  head_dim % 4 == 0.
+ */
+int hexi_attn_merge_lse(int64_t n_rows, int32_t n_q_heads, int32_t head_dim,
+                        float* o_acc, float* lse_acc, const float* o_part, const float* lse_part,
+                        void* o_final, int32_t o_final_dtype, void* hip_stream);
+
+/*
+ * One ring step backward with recomputation (App. A.1: attention work = forward + backward +
+ * recomputation; App. A.4 step shape).  P is recomputed from the saved GLOBAL lse of the merged
+ * forward:  P_ij = exp(s_ij - lse_i);  dV_j = sum_{h in group} sum_i P_ij dO_i;
+ *   dP_ij = <dO_i, v_j>;  dS_ij = P_ij (dP_ij - delta_i);  dQ_i += scale sum_j dS_ij k_j;
+ *   dK_j = scale sum_{h in group} sum_i dS_ij q_i.
+ * o is the merged fp32 forward output and is read only under HEXI_COMPUTE_DELTA (which fills
+ * delta for the whole shard before the chunk is processed); otherwise delta is an input.
+ * dq_acc (fp32) accumulates over calls: the caller zeroes it before the first chunk.  The adds into
+ * dq_acc are floating-point atomics, so their order (and the last bits) can vary between runs.
+ * dk, dv (fp32, this chunk's rows) are overwritten, or added to under HEXI_ACCUMULATE.  A chunk
+ * wholly in the shard's future writes zeros to dk/dv (nothing under HEXI_ACCUMULATE) and leaves
+ * dq_acc untouched.  d_o has the dtype and strides of q.
+ */
+int hexi_attn_bwd_chunk(const hexi_attn_desc* desc, const hexi_range* q_range, const hexi_range* kv_range,
+                        const void* q, const void* k, const void* v, const float* o, const void* d_o,
+                        const float* lse, float* delta,
+                        float* dq_acc, float* dk, float* dv, uint32_t flags,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of device workspace the chunk calls need for this descriptor and these lengths
+ * (currently 0: no kernel uses scratch memory). */
+size_t hexi_workspace_bytes(const hexi_attn_desc* desc, int64_t lq, int64_t lc);
+
+/* Description of the last error on the calling thread ("" if none). */
+const char* hexi_last_error(void);
+
+/* Library version string, e.g. "hexi-attn 0.1 (gfx950)". */
+const char* hexi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HEXI_ATTN_H */

@@ -1,0 +1,70 @@
+// gfx950 MFMA / LDS helpers shared by the bf16 forward and backward kernels.
+//
+// v_mfma_f32_32x32x16_bf16 operand layout (wave64; l32 = lane % 32, hh = lane / 32):
+//   A (32 x 16): lane holds row l32, contraction slots k = 8*hh + e, e = 0..7
+//   B (16 x 32): lane holds column l32, contraction slots k = 8*hh + e
+//   C (32 x 32): lane holds column l32; register r = 4*b + t holds row 8*b + 4*hh + t
+// The contraction index may be permuted freely as long as A and B agree.  Feeding accumulator
+// registers [8*x .. 8*x+7] of one lane straight back in as an operand therefore assigns slot
+// (hh, e) to accumulator row 16*x + 8*(e/4) + 4*hh + (e%4); the other operand is then fetched with
+// that same assignment.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+#define HEXI_LDS __attribute__((address_space(3)))
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// ds_read_b64_tr_b16: within each group of 16 lanes, lane i receives, for e = 0..3, the (i % 4)-th
+// 16-bit element of the 8-byte word addressed by lane 4*e + i/4 of its group.  With lane j
+// addressing element [row0 + j/4][col0 + 4*(j%4)] of a row-major tile, lane i ends up with the four
+// elements [row0 + e][col0 + i]: a 4 x 16 block read transposed.
+__device__ __forceinline__ s16x4 lds_read_tr16(const uint16_t* p)
+{
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 HEXI_LDS*)(p));
+}
+
+// Eight contraction slots for a lane from two transposed 4-row reads (rows row_a.. and row_b..).
+__device__ __forceinline__ bf16x8 lds_tr_pair(const uint16_t* pa, const uint16_t* pb)
+{
+    const s16x4 x = lds_read_tr16(pa), y = lds_read_tr16(pb);
+    s16x8 r = {x[0], x[1], x[2], x[3], y[0], y[1], y[2], y[3]};
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+__device__ __forceinline__ bf16x8 pack_bf16x8(float a0, float a1, float a2, float a3, float a4, float a5, float a6, float a7)
+{
+    bf16x8 r;
+    r[0] = (__bf16)a0; r[1] = (__bf16)a1; r[2] = (__bf16)a2; r[3] = (__bf16)a3;
+    r[4] = (__bf16)a4; r[5] = (__bf16)a5; r[6] = (__bf16)a6; r[7] = (__bf16)a7;
+    return r;
+}
+
+// Rounds 8 probabilities to bf16 operand slots and adds the ROUNDED values to `sum` (v_dot2c_f32_bf16
+// against a vector of ones), so that a normaliser built from `sum` matches the weights the MFMA
+// actually uses.
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ bf16x8 pack_bf16x8_sum(float a0, float a1, float a2, float a3, float a4, float a5, float a6, float a7, float& sum)
+{
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    const bf16x2 t0 = {(__bf16)a0, (__bf16)a1}, t1 = {(__bf16)a2, (__bf16)a3}, t2 = {(__bf16)a4, (__bf16)a5}, t3 = {(__bf16)a6, (__bf16)a7};
+    sum = __builtin_amdgcn_fdot2_f32_bf16(t0, ones, sum, false);
+    sum = __builtin_amdgcn_fdot2_f32_bf16(t1, ones, sum, false);
+    sum = __builtin_amdgcn_fdot2_f32_bf16(t2, ones, sum, false);
+    sum = __builtin_amdgcn_fdot2_f32_bf16(t3, ones, sum, false);
+    bf16x8 r = {t0[0], t0[1], t1[0], t1[1], t2[0], t2[1], t3[0], t3[1]};
+    return r;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }

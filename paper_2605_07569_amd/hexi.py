@@ -1,0 +1,181 @@
+"""Thin ctypes binding over libhexi_attn.so (the C ABI of include/hexi_attn.h).
+
+Argument marshalling only: every step of the attention path runs in the library's HIP kernels.
+Tensors are torch tensors used as device-memory handles (``data_ptr()``); the stream is torch's
+current HIP stream unless given.  There is no CPU fallback: if the library has not been built,
+loading raises.
+"""
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+HEXI_OK = 0
+HEXI_EINVAL, HEXI_EUNSUPPORTED, HEXI_EALIGN, HEXI_EWORKSPACE, HEXI_EHIP = -1, -2, -3, -4, -5
+HEXI_BF16, HEXI_F32 = 0, 1
+HEXI_ACCUMULATE, HEXI_COMPUTE_DELTA = 1, 2
+HEXI_TILE_EMPTY, HEXI_TILE_FULL, HEXI_TILE_PARTIAL = 0, 1, 2
+HEXI_MAX_SEGS = 16
+
+EXPORTS = ("hexi_shard_mask", "hexi_attn_fwd_chunk", "hexi_attn_merge_lse", "hexi_attn_bwd_chunk",
+           "hexi_workspace_bytes", "hexi_last_error", "hexi_version")
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhexi_attn.so")
+_lib = None
+
+
+class HexiError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"hexi error {code}: {msg}")
+        self.code = code
+
+
+class hexi_seg(ctypes.Structure):
+    _fields_ = [("start", ctypes.c_int64), ("len", ctypes.c_int64)]
+
+
+class hexi_range(ctypes.Structure):
+    _fields_ = [("n_segs", ctypes.c_int32), ("segs", ctypes.POINTER(hexi_seg))]
+
+
+class hexi_attn_desc(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("kv_of_q", ctypes.POINTER(ctypes.c_int32)), ("softmax_scale", ctypes.c_float),
+                ("q_stride_tok", ctypes.c_int64), ("q_stride_head", ctypes.c_int64),
+                ("kv_stride_tok", ctypes.c_int64), ("kv_stride_head", ctypes.c_int64)]
+
+
+def load():
+    """Loads the in-tree library; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_07569_amd.build` "
+                           "(hipcc, gfx950); there is no CPU fallback")
+    import torch  # noqa: F401  (loads the HIP runtime the library binds to)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, u32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32
+    rp, dp = ctypes.POINTER(hexi_range), ctypes.POINTER(hexi_attn_desc)
+    lib.hexi_shard_mask.argtypes = [rp, rp, i32, i32, vp, vp, vp, ctypes.POINTER(i64)]
+    lib.hexi_shard_mask.restype = ctypes.c_int
+    lib.hexi_attn_fwd_chunk.argtypes = [dp, rp, rp, vp, vp, vp, vp, vp, u32, vp, ctypes.c_size_t, vp]
+    lib.hexi_attn_fwd_chunk.restype = ctypes.c_int
+    lib.hexi_attn_merge_lse.argtypes = [i64, i32, i32, vp, vp, vp, vp, vp, i32, vp]
+    lib.hexi_attn_merge_lse.restype = ctypes.c_int
+    lib.hexi_attn_bwd_chunk.argtypes = [dp, rp, rp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp, ctypes.c_size_t, vp]
+    lib.hexi_attn_bwd_chunk.restype = ctypes.c_int
+    lib.hexi_workspace_bytes.argtypes = [dp, i64, i64]
+    lib.hexi_workspace_bytes.restype = ctypes.c_size_t
+    lib.hexi_last_error.restype = ctypes.c_char_p
+    lib.hexi_version.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(rc):
+    if rc != HEXI_OK:
+        raise HexiError(rc, load().hexi_last_error().decode())
+
+
+def make_range(segs: Sequence[Tuple[int, int]]):
+    """[(start, len), ...] -> (hexi_range, keepalive)."""
+    arr = (hexi_seg * max(1, len(segs)))(*[hexi_seg(int(s), int(n)) for s, n in segs])
+    return hexi_range(len(segs), arr), arr
+
+
+def make_desc(dtype, head_dim, n_q_heads, n_kv_heads, softmax_scale, q_strides, kv_strides, kv_of_q=None):
+    """q_strides / kv_strides: (token stride, head stride) in elements."""
+    keep = None
+    ptr = ctypes.POINTER(ctypes.c_int32)()
+    if kv_of_q is not None:
+        keep = (ctypes.c_int32 * len(kv_of_q))(*[int(x) for x in kv_of_q])
+        ptr = ctypes.cast(keep, ctypes.POINTER(ctypes.c_int32))
+    d = hexi_attn_desc(int(dtype), int(head_dim), int(n_q_heads), int(n_kv_heads), ptr, float(softmax_scale),
+                       int(q_strides[0]), int(q_strides[1]), int(kv_strides[0]), int(kv_strides[1]))
+    d._keep = keep
+    return d
+
+
+def desc_for(q, k, softmax_scale, kv_of_q=None):
+    """Descriptor for torch tensors q [Lq, nq, d] and k [Lc, nkv, d] (d contiguous)."""
+    import torch
+    assert q.dim() == 3 and k.dim() == 3 and q.stride(2) == 1 and k.stride(2) == 1
+    dt = {torch.bfloat16: HEXI_BF16, torch.float32: HEXI_F32}[q.dtype]
+    return make_desc(dt, q.shape[2], q.shape[1], k.shape[1], softmax_scale,
+                     (q.stride(0), q.stride(1)), (k.stride(0), k.stride(1)), kv_of_q)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    return ctypes.c_void_p(int(stream))
+
+
+def hexi_version():
+    return load().hexi_version().decode()
+
+
+def hexi_last_error():
+    return load().hexi_last_error().decode()
+
+
+def hexi_shard_mask(q_segs, kv_segs, tile_m=0, tile_n=0, want_pos=True, want_classes=True):
+    """Host bookkeeping -> dict(q_pos, kv_pos (int32 numpy), tile_class (uint8 [nm, nn]), n_pairs)."""
+    lib = load()
+    qr, _k1 = make_range(q_segs)
+    kr, _k2 = make_range(kv_segs)
+    lq, lc = sum(int(n) for _, n in q_segs), sum(int(n) for _, n in kv_segs)
+    q_pos = np.empty(max(lq, 0), dtype=np.int32) if want_pos else None
+    kv_pos = np.empty(max(lc, 0), dtype=np.int32) if want_pos else None
+    cls = None
+    if want_classes and tile_m > 0 and tile_n > 0:
+        cls = np.empty((-(-lq // tile_m), -(-lc // tile_n)), dtype=np.uint8)
+    n_pairs = ctypes.c_int64(0)
+    rc = lib.hexi_shard_mask(ctypes.byref(qr), ctypes.byref(kr), tile_m, tile_n,
+                             None if q_pos is None else q_pos.ctypes.data_as(ctypes.c_void_p),
+                             None if kv_pos is None else kv_pos.ctypes.data_as(ctypes.c_void_p),
+                             None if cls is None else cls.ctypes.data_as(ctypes.c_void_p),
+                             ctypes.byref(n_pairs))
+    _check(rc)
+    return dict(q_pos=q_pos, kv_pos=kv_pos, tile_class=cls, n_pairs=int(n_pairs.value))
+
+
+def hexi_attn_fwd_chunk(desc, q_segs, kv_segs, q, k, v, o, lse, flags=0, workspace=None, stream=None):
+    qr, _k1 = make_range(q_segs)
+    kr, _k2 = make_range(kv_segs)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().hexi_attn_fwd_chunk(ctypes.byref(desc), ctypes.byref(qr), ctypes.byref(kr), _ptr(q), _ptr(k), _ptr(v),
+                                      _ptr(o), _ptr(lse), flags, _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def hexi_attn_merge_lse(o_acc, lse_acc, o_part, lse_part, o_final=None, stream=None):
+    import torch
+    n_rows, nq, d = o_acc.shape
+    fdt = HEXI_F32
+    if o_final is not None:
+        fdt = {torch.bfloat16: HEXI_BF16, torch.float32: HEXI_F32}[o_final.dtype]
+    _check(load().hexi_attn_merge_lse(n_rows, nq, d, _ptr(o_acc), _ptr(lse_acc), _ptr(o_part), _ptr(lse_part),
+                                      _ptr(o_final), fdt, _stream(stream)))
+
+
+def hexi_attn_bwd_chunk(desc, q_segs, kv_segs, q, k, v, o, d_o, lse, delta, dq_acc, dk, dv, flags=0,
+                        workspace=None, stream=None):
+    qr, _k1 = make_range(q_segs)
+    kr, _k2 = make_range(kv_segs)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().hexi_attn_bwd_chunk(ctypes.byref(desc), ctypes.byref(qr), ctypes.byref(kr), _ptr(q), _ptr(k), _ptr(v),
+                                      _ptr(o), _ptr(d_o), _ptr(lse), _ptr(delta), _ptr(dq_acc), _ptr(dk), _ptr(dv),
+                                      flags, _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def hexi_workspace_bytes(desc, lq, lc):
+    return int(load().hexi_workspace_bytes(ctypes.byref(desc), lq, lc))
