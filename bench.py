@@ -1,0 +1,161 @@
+#!/usr/bin/env python3
+"""Benchmark of the chunked-ring attention hot path on one MI355X.
+
+One step = one pass of the whole hot path over one synthetic shard: forward replay of the KV chunk
+list (fwd_chunk with the fused LSE merge), Delta, backward replay (bwd_chunk per chunk).  Inputs are
+resident in HBM before the timed region.  Prints one JSON line: fwd+bwd TFLOP/s counted on unmasked
+(query, key) pairs only (4*d forward + 10*d backward flops per pair per q head), the roofline
+position of the dominant kernel (the bf16 backward kernel) measured with HIP events around its
+launches inside the timed region, and the fp64 CPU oracle timed on a bounded sample of the same
+workload as a reported baseline.
+"""
+import argparse
+import json
+import sys
+import time
+
+import torch
+
+PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16 MFMA peak: 256 CU x 2.4 GHz x 4096 flop/clk/CU
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# command (see profiles/); None until measured for a workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", type=int, default=2, help="shard configuration 1..5 (default 2: the 3B-like zigzag shard)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=0, help="rows per q segment for the oracle sample (0: auto)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU's share of the ring on one MI355X; --gpus above 1 is not supported "
+              "(no collectives are part of this build)", file=sys.stderr)
+        sys.exit(2)
+    from paper_2605_07569_amd import hexi, replay
+    from paper_2605_07569_amd import workloads as wl
+
+    hexi.load()   # raises if the HIP library is not built: no fallback path exists
+    torch.cuda.set_device(0)
+    w = wl.config(args.workload)
+    inputs = wl.make_inputs(w)
+    run = replay.ShardRun(w, inputs, "cuda:0", fused_merge=True)
+    n_pairs_chunk = [hexi.hexi_shard_mask(w.q_segs, ch, want_pos=False)["n_pairs"] for ch in w.chunks]
+    n_pairs = sum(n_pairs_chunk)
+    d, nq = w.head_dim, w.n_q_heads
+    flops_fwd = 4.0 * d * n_pairs * nq
+    flops_bwd = 10.0 * d * n_pairs * nq
+    live = [j for j, n in enumerate(n_pairs_chunk) if n > 0]       # chunks that launch the attention kernels
+
+    for _ in range(args.warmup):
+        run.step()
+    torch.cuda.synchronize()
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    fwd_ev, bwd_ev, kern_ev = [], [], []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        e0, e1, e2 = ev(), ev(), ev()
+        e0.record()
+        run.forward()
+        e1.record()
+        # backward replay with events around every bwd_chunk launch (same stream as the kernels)
+        run.dq.zero_()
+        for j, ch in enumerate(w.chunks):
+            flags = hexi.HEXI_COMPUTE_DELTA if j == 0 else 0
+            ka, kb = ev(), ev()
+            ka.record()
+            hexi.hexi_attn_bwd_chunk(run.desc[j], w.q_segs, ch, run.q, run.k[j], run.v[j], run.o, run.d_o,
+                                     run.lse, run.delta, run.dq, run.dk[j], run.dv[j], flags=flags)
+            kb.record()
+            if j in live and j != 0:
+                kern_ev.append((j, ka, kb))
+        e2.record()
+        fwd_ev.append((e0, e1))
+        bwd_ev.append((e1, e2))
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    fwd_ms = sum(a.elapsed_time(b) for a, b in fwd_ev) / args.steps
+    bwd_ms = sum(a.elapsed_time(b) for a, b in bwd_ev) / args.steps
+    tflops = (flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12
+
+    # dominant kernel: bf16 backward.  Per launch: algorithmic flops = 10*d*nq*(pairs of that chunk).
+    if kern_ev:
+        k_ms = sum(a.elapsed_time(b) for _, a, b in kern_ev) / len(kern_ev)
+        k_flops = sum(10.0 * d * nq * n_pairs_chunk[j] for j, _, _ in kern_ev) / len(kern_ev)
+    else:  # single live chunk: fall back to the whole backward replay
+        k_ms, k_flops = bwd_ms, flops_bwd
+    achieved = k_flops / (k_ms * 1e-3) / 1e12
+    is_bf16 = w.dtype == "bf16"
+    peak = PEAK_BF16_TFLOPS if is_bf16 else 157.3
+    roofline = {"bound": "mfma" if is_bf16 else "alu", "kernel": "bwd_bf16_kernel" if is_bf16 else "bwd_f32_kernel",
+                "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(w.name), "launch_ms": round(k_ms, 4),
+                "flops_per_launch": k_flops}
+
+    out = {"metric": "attention fwd+bwd TFLOP/s per shard on 1 MI355X; % of bf16 MFMA peak",
+           "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": w.dtype, "data": "synthetic",
+           "config": {"workload": w.name, "note": w.note, "n_q_heads": nq, "n_kv_heads": w.n_kv_heads, "head_dim": d,
+                      "q_rows": w.lq, "kv_chunks": len(w.chunks), "unmasked_pairs_per_head": n_pairs,
+                      "counted_tflop_per_step": round((flops_fwd + flops_bwd) / 1e12, 3)},
+           "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
+           "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4),
+           "fwd_tflops": round(flops_fwd / (fwd_ms * 1e-3) / 1e12, 2),
+           "bwd_tflops": round(flops_bwd / (bwd_ms * 1e-3) / 1e12, 2),
+           "roofline": roofline}
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, inputs, args.cpu_rows)
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(w, inputs, rows_per_seg):
+    """The fp64 oracle, as it stands, on a bounded sample: a few rows of every q segment, all local
+    heads, each row against all its visible keys, forward + backward.  Rate in the metric's unit,
+    counting the same 14*d flops per unmasked pair."""
+    import numpy as np
+    import oracle
+    from paper_2605_07569_amd import workloads as wl
+    q_pos_all = wl.seg_positions(w.q_segs).numpy()
+    if rows_per_seg <= 0:
+        # aim at ~1e8 (row, key, head) triples: 10-30 s of oracle work on 16 cores
+        budget = 1.0e8
+        per_row = float(np.mean(q_pos_all + 1)) * w.n_q_heads
+        rows_per_seg = max(1, int(budget / per_row / len(w.q_segs)))
+    rows, off = [], 0
+    for s, n in w.q_segs:
+        take = min(rows_per_seg, n)
+        rows.extend(off + np.linspace(0, n - 1, take).astype(np.int64))
+        off += n
+    rows = np.array(sorted(set(int(r) for r in rows)), dtype=np.int64)
+    q_pos = q_pos_all[rows]
+    n_keys = int(q_pos.max()) + 1
+    f64 = lambda t: t.to(torch.float64).numpy()
+    q, d_o = f64(inputs["q"][rows]), f64(inputs["d_o"][rows])
+    k, v = f64(inputs["k"][:n_keys]), f64(inputs["v"][:n_keys])
+    kv_pos = np.arange(n_keys, dtype=np.int64)
+    t0 = time.perf_counter()
+    oracle.attn_fwd(q, q_pos, k, v, kv_pos, w.scale, w.kv_of_q)
+    oracle.attn_bwd(q, q_pos, k, v, kv_pos, d_o, w.scale, w.kv_of_q)
+    dt = time.perf_counter() - t0
+    pairs = float(np.sum(q_pos + 1))
+    flops = 14.0 * w.head_dim * pairs * w.n_q_heads
+    return {"value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{len(rows)} of {w.lq} shard rows (evenly spaced in each q segment) x all {w.n_q_heads} local heads, "
+                      f"each against all its visible keys, fwd+bwd in fp64; {dt:.1f} s",
+            "seconds": round(dt, 2)}
+
+
+if __name__ == "__main__":
+    main()
