@@ -1,12 +1,22 @@
-// bf16 backward ring step for gfx950: one workgroup (4 wavefronts) per (128-key tile, kv head).
+// bf16 backward ring step for gfx950: one workgroup (4 wavefronts, one per SIMD) per
+// (128-key tile, q head).
 //
 // The workgroup keeps its K and V rows in registers as MFMA operands and its dK / dV tiles in
-// accumulators while it sweeps the q tiles (64 rows) of every q head of the GQA group that can see
-// the key tile.  Per q tile: S = Q K^T and dP = dO V^T (keys across lanes, query rows in-lane),
-// P = exp2(S*scale*log2e - LSE*log2e) from the saved global LSE, dS = P (dP - Delta); the
-// accumulator registers holding P and dS are already in operand order for dV += P^T dO and
-// dK += dS^T Q (dO and Q fetched with transposed LDS reads).  dS is written to LDS once (bf16,
-// transposed) to be re-read as the A operand of dQ = dS K, which goes out through fp32 atomics.
+// accumulators while it sweeps the 64-row q tiles that can see the key tile.  Per q tile:
+// S = Q K^T and dP = dO V^T (keys across lanes, query rows in-lane), P = exp2(S*scale*log2e -
+// LSE*log2e) from the saved global LSE, dS = P (dP - Delta); the accumulator registers holding P
+// and dS are already in operand order for dV += P^T dO and dK += dS^T Q (dO and Q fetched with
+// transposed LDS reads).  dS is written to LDS once (bf16, transposed) and re-read as the A operand
+// of dQ = dS K, which goes out through fp32 atomics.
+//
+// Pipeline: Q / dO tiles are double-buffered in LDS and fetched one tile ahead with direct
+// global->LDS loads; the dQ product of tile t-1 is issued at the start of iteration t, so one
+// barrier per iteration suffices.  LDS tiles are XOR-swizzled (no padding) so that both the 128-bit
+// row reads and the transposed 64-bit reads are bank-conflict free.
+//
+// The q heads of a GQA group run in different workgroups and add their dK / dV tiles with fp32
+// atomics (plain stores when the group has a single head), so dk/dv must be zero-filled (or hold
+// the running sum under HEXI_ACCUMULATE) before the launch.
 #include "hexi_internal.h"
 #include "hexi_mfma.h"
 
@@ -15,43 +25,65 @@ namespace {
 constexpr int D = 128;
 constexpr int TN = 128;          // keys per workgroup (32 per wavefront)
 constexpr int TM = 64;           // q rows per inner tile
-constexpr int QSTR = D + 8;      // LDS row stride of Q / dO / K staging (elements)
-constexpr int SSTR = TM + 8;     // LDS row stride of dS^T [key][q row]
 constexpr float LOG2E = 1.4426950408889634f;
 
-__global__ void __launch_bounds__(256) bwd_bf16_kernel(const BwdArgs a)
+// [rows][128] bf16 tile, 16-byte chunk c of row r stored at chunk position c ^ swz_row(r)
+__device__ __forceinline__ int swz_row(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+// dS^T tile [128 keys][64 q rows] bf16: 8-byte word w (4 consecutive q rows) of key row r at word position
+// w ^ swz_ds(r)
+__device__ __forceinline__ int swz_ds(int r) { const int y = (r >> 1) & 15; return y ^ ((y & 1) << 3); }
+
+struct BwdSmem {
+    uint16_t q[2][TM * D];        // 2 x 16 KB
+    uint16_t g[2][TM * D];        // dO, 2 x 16 KB
+    uint16_t ds[2][TN * TM];      // dS^T, 2 x 16 KB
+    float lse[2][TM];
+    float delta[2][TM];
+    int qpos[2][TM];
+};
+
+template <bool ATOMIC_DKV>
+__global__ void __launch_bounds__(256) bwd_bf16_kernel(const BwdArgs a, const int n_kv_tiles)
 {
     const AttnGeom& g = a.g;
-    __shared__ __attribute__((aligned(16))) uint16_t Qs[TM * QSTR];
-    __shared__ __attribute__((aligned(16))) uint16_t Gs[TM * QSTR];      // dO tile
-    __shared__ __attribute__((aligned(16))) uint16_t dSt[TN * SSTR];     // dS^T, bf16
-    __shared__ __attribute__((aligned(16))) uint16_t Kst[TN * QSTR];     // K staging (start of kernel only)
-    __shared__ __attribute__((aligned(16))) float lse_s[TM];
-    __shared__ __attribute__((aligned(16))) float delta_s[TM];
-    __shared__ __attribute__((aligned(16))) int qpos_s[TM];
+    __shared__ __attribute__((aligned(1024))) BwdSmem sm;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hh = lane >> 5;
     const int grp2 = (lane >> 4) & 1, j16 = lane & 15;
-    const int kvh = blockIdx.y;
-    const int col0 = blockIdx.x * TN;
+
+    // Work mapping: consecutive workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a
+    // contiguous range of (head, key tile) units so that the workgroups sharing an L2 stream the
+    // same head's Q / dO tiles.
+    const int n_units = g.nq * n_kv_tiles;
+    int unit = blockIdx.x;
+    {
+        const int per = n_units / 8, rem = n_units % 8;
+        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        // XCD x owns per + (x < rem) units starting at x*per + min(x, rem)
+        unit = xcd * per + (xcd < rem ? xcd : rem) + slot;
+    }
+    const int h = unit / n_kv_tiles;
+    const int kv_tile = unit - h * n_kv_tiles;
+    const int kvh = g.kv_of_q[h];
+    const int col0 = kv_tile * TN;
     const int my_col = col0 + 32 * wave + l32;
     const int my_col_c = my_col < g.lc ? my_col : g.lc - 1;
     const int my_kpos = my_col < g.lc ? seg_pos_of_row(g.ks, my_col) : 0x7fffffff;
 
-    const uint16_t* q = static_cast<const uint16_t*>(a.q);
-    const uint16_t* go = static_cast<const uint16_t*>(a.d_o);
+    const uint16_t* q = static_cast<const uint16_t*>(a.q) + (long long)h * g.q_stride_head;
+    const uint16_t* go = static_cast<const uint16_t*>(a.d_o) + (long long)h * g.q_stride_head;
     const uint16_t* k = static_cast<const uint16_t*>(a.k) + (long long)kvh * g.kv_stride_head;
     const uint16_t* v = static_cast<const uint16_t*>(a.v) + (long long)kvh * g.kv_stride_head;
+    const float* lse_h = a.lse + (long long)h * g.lq;
+    const float* delta_h = a.delta + (long long)h * g.lq;
 
     // q rows that see at least one key of the tile form a suffix of the shard; rows that see all of
     // its keys form a (shorter) suffix
     const int last_col = (col0 + TN < g.lc ? col0 + TN : g.lc) - 1;
     const int k_min = seg_pos_of_row(g.ks, col0), k_max = seg_pos_of_row(g.ks, last_col);
-    const int first_row = seg_rows_le(g.qs, k_min - 1);
-    const int first_full_row = seg_rows_le(g.qs, k_max - 1);
-    const int qt_begin = first_row / TM;
-    const int qt_full = (col0 + TN <= g.lc) ? (first_full_row + TM - 1) / TM : 0x7fffffff;
+    const int qt_begin = seg_rows_le(g.qs, k_min - 1) / TM;
+    const int qt_full = (col0 + TN <= g.lc) ? (seg_rows_le(g.qs, k_max - 1) + TM - 1) / TM : 0x7fffffff;
     const int n_qtiles = (g.lq + TM - 1) / TM;
 
     // K^T and V^T operand fragments of S = Q K^T and dP = dO V^T: lane (key l32, half hh) holds
@@ -66,19 +98,27 @@ __global__ void __launch_bounds__(256) bwd_bf16_kernel(const BwdArgs a)
         }
     }
     // K operand fragments of dQ = dS K for this wavefront's 32 output columns d = 32*wave + l32:
-    // slot (hh, e) of step u is key 16*u + 8*hh + e, fetched transposed from the staged tile
-#pragma unroll
-    for (int pass = 0; pass < 8; ++pass) {
-        const int r = (tid >> 4) + 16 * pass, c = tid & 15;
-        const int col = col0 + r < g.lc ? col0 + r : g.lc - 1;
-        *reinterpret_cast<uint4*>(&Kst[r * QSTR + c * 8]) = *reinterpret_cast<const uint4*>(k + (long long)col * g.kv_stride_tok + c * 8);
-    }
-    __syncthreads();
+    // slot (hh, e) of step u is key 16*u + 8*hh + e, fetched transposed from a staged copy of the
+    // key tile (staged in the dS / q buffers, which are not in use yet)
     bf16x8 kq[8];
+    {
+        uint16_t* kst = &sm.q[0][0];    // 128 x 128 bf16 = 32 KB = q[0] and q[1]
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-        const uint16_t* p = &Kst[(16 * u + 8 * hh + (j16 >> 2)) * QSTR + 32 * wave + 16 * grp2 + 4 * (j16 & 3)];
-        kq[u] = lds_tr_pair(p, p + 4 * QSTR);
+        for (int pass = 0; pass < 8; ++pass) {
+            const int r = (tid >> 4) + 16 * pass, c = tid & 15;
+            const int col = col0 + r < g.lc ? col0 + r : g.lc - 1;
+            *reinterpret_cast<uint4*>(&kst[r * D + ((c ^ swz_row(r)) << 3)]) =
+                *reinterpret_cast<const uint4*>(k + (long long)col * g.kv_stride_tok + c * 8);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int r = 16 * u + 8 * hh + (j16 >> 2);
+            const int c = 4 * wave + 2 * grp2 + ((j16 & 3) >> 1);
+            kq[u] = lds_tr_pair(&kst[r * D + ((c ^ swz_row(r)) << 3) + 4 * (j16 & 1)],
+                                &kst[(r + 4) * D + ((c ^ swz_row(r + 4)) << 3) + 4 * (j16 & 1)]);
+        }
+        __syncthreads();
     }
 
     f32x16 dk_acc[4], dv_acc[4];
@@ -88,112 +128,234 @@ __global__ void __launch_bounds__(256) bwd_bf16_kernel(const BwdArgs a)
         for (int r = 0; r < 16; ++r) { dk_acc[db][r] = 0.f; dv_acc[db][r] = 0.f; }
     const float scale_log2 = g.scale * LOG2E;
 
-    for (int h = 0; h < g.nq; ++h) {
-        if (g.kv_of_q[h] != kvh) continue;
-        for (int qt = qt_begin; qt < n_qtiles; ++qt) {
-            const int row0 = qt * TM;
-            const bool partial = qt < qt_full;
-            __syncthreads();
+    // Direct global->LDS fetch of one q tile (Q and dO, 16 KB each): 16 wave-instructions of 1 KB per
+    // tensor, 4 per wavefront; lane L of instruction i fills chunk position L%16 of row 4*i + L/16.
+    // The loads are issued through inline assembly so that the compiler does not serialise later
+    // LDS reads of the OTHER buffer behind them; they are waited for explicitly (vmcnt(0)) right
+    // before the barrier that publishes the tile.
+    int fetch_off[4];
 #pragma unroll
-            for (int pass = 0; pass < 4; ++pass) {
-                const int r = (tid >> 4) + 16 * pass, c = tid & 15;
+    for (int i = 0; i < 4; ++i) {
+        const int r = (wave * 4 + i) * 4 + (lane >> 4);
+        fetch_off[i] = r * (int)g.q_stride_tok + (((lane & 15) ^ swz_row(r)) << 3);
+    }
+    const uint32_t lds_q = (uint32_t)(uintptr_t)(&sm.q[0][0]), lds_g = (uint32_t)(uintptr_t)(&sm.g[0][0]);
+    const uint32_t lds_lse = (uint32_t)(uintptr_t)(&sm.lse[0][0]), lds_delta = (uint32_t)(uintptr_t)(&sm.delta[0][0]);
+    auto fetch_tile = [&](int qt, int buf) {
+        const int row0 = qt * TM;
+        const uint32_t wq = __builtin_amdgcn_readfirstlane(lds_q + buf * (TM * D * 2) + wave * 4096);
+        const uint32_t wg = __builtin_amdgcn_readfirstlane(lds_g + buf * (TM * D * 2) + wave * 4096);
+        if (row0 + TM <= g.lq) {
+            const uint16_t* qb = q + (long long)row0 * g.q_stride_tok;
+            const uint16_t* gb = go + (long long)row0 * g.q_stride_tok;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                lds_dma16(qb + fetch_off[i], wq + i * 1024);
+                lds_dma16(gb + fetch_off[i], wg + i * 1024);
+            }
+        } else {   // ragged last tile: clamp the row index (the extra rows are masked out through their position)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int r = (wave * 4 + i) * 4 + (lane >> 4);
+                const int c = (lane & 15) ^ swz_row(r);
                 const int row = row0 + r < g.lq ? row0 + r : g.lq - 1;
-                const long long off = (long long)row * g.q_stride_tok + (long long)h * g.q_stride_head + c * 8;
-                const uint4 qx = *reinterpret_cast<const uint4*>(q + off);
-                const uint4 gx = *reinterpret_cast<const uint4*>(go + off);
-                *reinterpret_cast<uint4*>(&Qs[r * QSTR + c * 8]) = qx;
-                *reinterpret_cast<uint4*>(&Gs[r * QSTR + c * 8]) = gx;
+                const long long off = (long long)row * g.q_stride_tok + c * 8;
+                lds_dma16(q + off, wq + i * 1024);
+                lds_dma16(go + off, wg + i * 1024);
             }
-            if (tid < TM) {
-                const bool ok = row0 + tid < g.lq;
-                const float l = ok ? a.lse[(long long)h * g.lq + row0 + tid] : INFINITY;
-                lse_s[tid] = (l == -INFINITY) ? INFINITY : l * LOG2E;   // rows that see nothing: P = 0
-                delta_s[tid] = ok ? a.delta[(long long)h * g.lq + row0 + tid] : 0.f;
-                qpos_s[tid] = ok ? seg_pos_of_row(g.qs, row0 + tid) : -1;
-            }
-            __syncthreads();
+        }
+        // per-row scalars: one 4-byte-per-lane instruction each (LSE by wavefront 0, Delta by wavefront 1)
+        if (wave < 2) {
+            const int row = row0 + lane < g.lq ? row0 + lane : g.lq - 1;
+            const float* src = (wave == 0 ? lse_h : delta_h) + row;
+            lds_dma4(src, __builtin_amdgcn_readfirstlane((wave == 0 ? lds_lse : lds_delta) + buf * (TM * 4)));
+        }
+        // global positions of the tile's rows, only for tiles that need masking
+        if (wave == 2 && (qt < qt_full || row0 + TM > g.lq))
+            sm.qpos[buf][lane] = row0 + lane < g.lq ? seg_pos_of_row(g.qs, row0 + lane) : -1;
+    };
 
-            // S[q][key] and dP[q][key]: two 32-row q blocks, this wavefront's 32 keys
-            f32x16 s[2], dp[2];
+    // dQ[q][d] of a finished tile from its dS^T in LDS; this wavefront owns d = 32*wave + l32
+    auto dq_tile = [&](int qt, int buf) {
+        const int row0 = qt * TM;
+        f32x16 dq[2];
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < 2; ++b)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) { s[b][r] = 0.f; dp[b][r] = 0.f; }
+            for (int r = 0; r < 16; ++r) dq[b][r] = 0.f;
+        const uint16_t* ds = &sm.ds[buf][0];
+        auto load_sf = [&](int st) {
+            const int u = st >> 1, b = st & 1;
+            const int r = 16 * u + 8 * hh + (j16 >> 2);
+            const int w = 8 * b + 4 * grp2 + (j16 & 3);
+            return lds_tr_pair(&ds[r * TM + ((w ^ swz_ds(r)) << 2)], &ds[(r + 4) * TM + ((w ^ swz_ds(r + 4)) << 2)]);
+        };
+        constexpr int PF = 4;
+        bf16x8 ring[PF];
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
+        for (int st = 0; st < PF; ++st) ring[st] = load_sf(st);
 #pragma unroll
-                for (int b = 0; b < 2; ++b) {
-                    const bf16x8 qa = *reinterpret_cast<const bf16x8*>(&Qs[(32 * b + l32) * QSTR + 16 * ks + 8 * hh]);
-                    const bf16x8 ga = *reinterpret_cast<const bf16x8*>(&Gs[(32 * b + l32) * QSTR + 16 * ks + 8 * hh]);
-                    s[b] = mfma32(qa, kf[ks], s[b]);
-                    dp[b] = mfma32(ga, vf[ks], dp[b]);
-                }
-            }
-            // P and dS in place (s <- P, dp <- dS); in-lane row index i = 32*b + 8*(r/4) + 4*hh + r%4
-#pragma unroll
-            for (int b = 0; b < 2; ++b)
-#pragma unroll
-                for (int rb = 0; rb < 4; ++rb) {
-                    const int i0 = 32 * b + 8 * rb + 4 * hh;
-                    const f32x4 l4 = *reinterpret_cast<const f32x4*>(&lse_s[i0]);
-                    const f32x4 d4 = *reinterpret_cast<const f32x4*>(&delta_s[i0]);
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        float p = fast_exp2(s[b][4 * rb + t] * scale_log2 - l4[t]);
-                        if (partial && my_kpos > qpos_s[i0 + t]) p = 0.f;
-                        s[b][4 * rb + t] = p;
-                        dp[b][4 * rb + t] = p * (dp[b][4 * rb + t] - d4[t]);
-                    }
-                }
-            // dS^T to LDS for the dQ product: row = key, 4 consecutive q rows per 8-byte store
-#pragma unroll
-            for (int b = 0; b < 2; ++b)
-#pragma unroll
-                for (int rb = 0; rb < 4; ++rb) {
-                    bf16x4 w;
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) w[t] = (__bf16)dp[b][4 * rb + t];
-                    *reinterpret_cast<bf16x4*>(&dSt[(32 * wave + l32) * SSTR + 32 * b + 8 * rb + 4 * hh]) = w;
-                }
-            // dV += P^T dO, dK += dS^T Q over four 16-row steps
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int b = u >> 1, x = (u & 1) * 8;
-                const bf16x8 pf = pack_bf16x8(s[b][x], s[b][x + 1], s[b][x + 2], s[b][x + 3], s[b][x + 4], s[b][x + 5], s[b][x + 6], s[b][x + 7]);
-                const bf16x8 df = pack_bf16x8(dp[b][x], dp[b][x + 1], dp[b][x + 2], dp[b][x + 3], dp[b][x + 4], dp[b][x + 5], dp[b][x + 6], dp[b][x + 7]);
-                const int roff = (16 * u + 4 * hh + (j16 >> 2)) * QSTR + 16 * grp2 + 4 * (j16 & 3);
-#pragma unroll
-                for (int db = 0; db < 4; ++db) {
-                    const bf16x8 gf = lds_tr_pair(&Gs[roff + 32 * db], &Gs[roff + 32 * db + 8 * QSTR]);
-                    dv_acc[db] = mfma32(pf, gf, dv_acc[db]);
-                    const bf16x8 qf = lds_tr_pair(&Qs[roff + 32 * db], &Qs[roff + 32 * db + 8 * QSTR]);
-                    dk_acc[db] = mfma32(df, qf, dk_acc[db]);
-                }
-            }
-            __syncthreads();
-            // dQ[q][d] for d = 32*wave + l32: contraction over all 128 keys of the tile
-            f32x16 dq[2];
-#pragma unroll
-            for (int b = 0; b < 2; ++b)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) dq[b][r] = 0.f;
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-#pragma unroll
-                for (int b = 0; b < 2; ++b) {
-                    const uint16_t* p = &dSt[(16 * u + 8 * hh + (j16 >> 2)) * SSTR + 32 * b + 16 * grp2 + 4 * (j16 & 3)];
-                    const bf16x8 sf = lds_tr_pair(p, p + 4 * SSTR);
-                    dq[b] = mfma32(sf, kq[u], dq[b]);
-                }
-            }
+        for (int st = 0; st < 16; ++st) {
+            const bf16x8 sf = ring[st % PF];
+            if (st + PF < 16) ring[st % PF] = load_sf(st + PF);
+            dq[st & 1] = mfma32(sf, kq[st >> 1], dq[st & 1]);
+        }
+        // row i = 32*b + 8*rb + 4*hh + t: the (b, rb, t) part of the address is wave-uniform
+        const long long row_stride = (long long)g.nq * D;
+        float* tile_base = a.dq + ((long long)row0 * g.nq + h) * D;
+        const int lane_off = 4 * hh * g.nq * D + 32 * wave + l32;
+#ifdef EXP_NO_ATOMICS
+        if (g.scale != 12345.f) { if (dq[0][0] + dq[1][5] == 1.2345f) a.dq[0] = 1.f; } else
+#endif
+        if (row0 + TM <= g.lq) {
 #pragma unroll
             for (int b = 0; b < 2; ++b)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int row = row0 + 32 * b + 8 * (r >> 2) + 4 * hh + (r & 3);
-                    if (row < g.lq) unsafeAtomicAdd(a.dq + ((long long)row * g.nq + h) * D + 32 * wave + l32, dq[b][r] * g.scale);
+                    float* rowp = tile_base + (32 * b + 8 * (r >> 2) + (r & 3)) * row_stride;
+                    global_atomic_add(rowp + lane_off, dq[b][r] * g.scale);
+                }
+        } else {
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int i = 32 * b + 8 * (r >> 2) + 4 * hh + (r & 3);
+                    float* rowp = tile_base + (32 * b + 8 * (r >> 2) + (r & 3)) * row_stride;
+                    if (row0 + i < g.lq) global_atomic_add(rowp + lane_off, dq[b][r] * g.scale);
                 }
         }
+    };
+
+    const int sw_l32 = swz_row(l32);
+    // The q tiles are visited in rotated order, each key tile starting at a different q tile, so
+    // that workgroups running side by side do not add into the same dQ rows at the same moment.
+    const int n_it = n_qtiles - qt_begin;
+#ifndef EXP_STAGGER
+#define EXP_STAGGER 0
+#endif
+    const int rot = n_it > 0 ? (int)(((long long)kv_tile * EXP_STAGGER) % n_it) : 0;
+    auto tile_of = [&](int it) { int t = it + rot; if (t >= n_it) t -= n_it; return qt_begin + t; };
+    if (n_it > 0) fetch_tile(tile_of(0), 0);
+    for (int it = 0; it < n_it; ++it) {
+        const int qt = tile_of(it);
+        const int buf = it & 1;
+        const bool partial = qt < qt_full || qt * TM + TM > g.lq;
+        // publish tile qt: wait for this wavefront's outstanding global->LDS loads, then barrier
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+#ifdef EXP_NO_FETCH
+        if (it + 1 < n_it && g.scale == 12345.f) fetch_tile(tile_of(it + 1), buf ^ 1);
+#else
+        if (it + 1 < n_it) fetch_tile(tile_of(it + 1), buf ^ 1);
+#endif
+#ifndef EXP_NO_DQ
+        if (it > 0) dq_tile(tile_of(it - 1), buf ^ 1);
+#endif
+
+        const uint16_t* Qs = &sm.q[buf][0];
+        const uint16_t* Gs = &sm.g[buf][0];
+        // S[q][key] and dP[q][key]: two 32-row q blocks, this wavefront's 32 keys
+        f32x16 s[2], dp[2];
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { s[b][r] = 0.f; dp[b][r] = 0.f; }
+        {
+            auto frag_off = [&](int st) { return (32 * (st & 1) + l32) * D + (((2 * (st >> 1) + hh) ^ sw_l32) << 3); };
+            constexpr int PF = 3;
+            bf16x8 qr[PF], gr[PF];
+#pragma unroll
+            for (int st = 0; st < PF; ++st) {
+                qr[st] = *reinterpret_cast<const bf16x8*>(&Qs[frag_off(st)]);
+                gr[st] = *reinterpret_cast<const bf16x8*>(&Gs[frag_off(st)]);
+            }
+#pragma unroll
+            for (int st = 0; st < 16; ++st) {
+                const bf16x8 qa = qr[st % PF], ga = gr[st % PF];
+                if (st + PF < 16) {
+                    qr[st % PF] = *reinterpret_cast<const bf16x8*>(&Qs[frag_off(st + PF)]);
+                    gr[st % PF] = *reinterpret_cast<const bf16x8*>(&Gs[frag_off(st + PF)]);
+                }
+                s[st & 1] = mfma32(qa, kf[st >> 1], s[st & 1]);
+                dp[st & 1] = mfma32(ga, vf[st >> 1], dp[st & 1]);
+            }
+        }
+        // P and dS in place (s <- P, dp <- dS); in-lane row index i = 32*b + 8*rb + 4*hh + t.
+        // Rows whose LSE is -inf see nothing anywhere, so they are masked in every tile they appear in.
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb) {
+                const int i0 = 32 * b + 8 * rb + 4 * hh;
+                const f32x4 l4 = *reinterpret_cast<const f32x4*>(&sm.lse[buf][i0]);
+                const f32x4 d4 = *reinterpret_cast<const f32x4*>(&sm.delta[buf][i0]);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    float p = fast_exp2(s[b][4 * rb + t] * scale_log2 - l4[t] * LOG2E);
+                    if (partial && my_kpos > sm.qpos[buf][i0 + t]) p = 0.f;
+                    s[b][4 * rb + t] = p;
+                    dp[b][4 * rb + t] = p * (dp[b][4 * rb + t] - d4[t]);
+                }
+            }
+        // dS^T to LDS for the dQ product of the next iteration: key row, word = 4 consecutive q rows
+        {
+            uint16_t* ds = &sm.ds[buf][0];
+            const int r = 32 * wave + l32;
+            const int sw = swz_ds(r);
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int rb = 0; rb < 4; ++rb) {
+                    bf16x4 w4;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) w4[t] = (__bf16)dp[b][4 * rb + t];
+                    const int w = 8 * b + 2 * rb + hh;
+                    *reinterpret_cast<bf16x4*>(&ds[r * TM + ((w ^ sw) << 2)]) = w4;
+                }
+        }
+        // dV += P^T dO, dK += dS^T Q over four 16-row steps x four 32-column blocks
+        {
+            bf16x8 pf[4], df[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int b = u >> 1, x = (u & 1) * 8;
+                pf[u] = pack_bf16x8(s[b][x], s[b][x + 1], s[b][x + 2], s[b][x + 3], s[b][x + 4], s[b][x + 5], s[b][x + 6], s[b][x + 7]);
+                df[u] = pack_bf16x8(dp[b][x], dp[b][x + 1], dp[b][x + 2], dp[b][x + 3], dp[b][x + 4], dp[b][x + 5], dp[b][x + 6], dp[b][x + 7]);
+            }
+            const int jj = j16 >> 2, cl = 2 * grp2 + ((j16 & 3) >> 1);
+            auto tr_off = [&](int st, int second) {
+                const int u = st >> 2, db = st & 3;
+                const int r = 16 * u + 4 * hh + jj + 8 * second;
+                const int pos = (((db ^ jj) << 2) | (cl ^ (hh + 2 * second)));
+                return r * D + (pos << 3) + 4 * (j16 & 1);
+            };
+            constexpr int PF = 3;
+            bf16x8 gr[PF], qr[PF];
+#pragma unroll
+            for (int st = 0; st < PF; ++st) {
+                gr[st] = lds_tr_pair(&Gs[tr_off(st, 0)], &Gs[tr_off(st, 1)]);
+                qr[st] = lds_tr_pair(&Qs[tr_off(st, 0)], &Qs[tr_off(st, 1)]);
+            }
+#pragma unroll
+#ifdef EXP_NO_DVDK
+            for (int st = 0; st < (g.scale == 12345.f ? 16 : 0); ++st) {
+#else
+            for (int st = 0; st < 16; ++st) {
+#endif
+                const bf16x8 gf = gr[st % PF], qf = qr[st % PF];
+                if (st + PF < 16) {
+                    gr[st % PF] = lds_tr_pair(&Gs[tr_off(st + PF, 0)], &Gs[tr_off(st + PF, 1)]);
+                    qr[st % PF] = lds_tr_pair(&Qs[tr_off(st + PF, 0)], &Qs[tr_off(st + PF, 1)]);
+                }
+                dv_acc[st & 3] = mfma32(pf[st >> 2], gf, dv_acc[st & 3]);
+                dk_acc[st & 3] = mfma32(df[st >> 2], qf, dk_acc[st & 3]);
+            }
+        }
+    }
+    if (n_it > 0) {
+        __syncthreads();
+        dq_tile(tile_of(n_it - 1), (n_it - 1) & 1);
     }
 
     // dK / dV: lane holds column d = 32*db + l32; register r holds key 32*wave + 8*(r/4) + 4*hh + r%4
@@ -205,7 +367,14 @@ __global__ void __launch_bounds__(256) bwd_bf16_kernel(const BwdArgs a)
             if (col < g.lc) {
                 const long long idx = ((long long)col * g.nkv + kvh) * D + 32 * db + l32;
                 const float kk = dk_acc[db][r] * g.scale, vv = dv_acc[db][r];
-                if (a.accumulate) { a.dk[idx] += kk; a.dv[idx] += vv; } else { a.dk[idx] = kk; a.dv[idx] = vv; }
+                if (ATOMIC_DKV) {
+                    global_atomic_add(a.dk + idx, kk);
+                    global_atomic_add(a.dv + idx, vv);
+                } else if (a.accumulate) {
+                    a.dk[idx] += kk; a.dv[idx] += vv;
+                } else {
+                    a.dk[idx] = kk; a.dv[idx] = vv;
+                }
             }
         }
 }
@@ -214,7 +383,25 @@ __global__ void __launch_bounds__(256) bwd_bf16_kernel(const BwdArgs a)
 
 hipError_t hexi_launch_bwd_bf16(const BwdArgs& a, hipStream_t s)
 {
-    dim3 grid((a.g.lc + TN - 1) / TN, a.g.nkv);
-    bwd_bf16_kernel<<<grid, 256, 0, s>>>(a);
+    const int n_kv_tiles = (a.g.lc + TN - 1) / TN;
+    // does any kv head serve more than one q head?  then the heads' dK/dV tiles are summed atomically
+    int cnt[HEXI_MAX_HEADS] = {0};
+    bool shared = false, unused = false;
+    for (int h = 0; h < a.g.nq; ++h) shared |= (++cnt[a.g.kv_of_q[h]] > 1);
+    for (int kh = 0; kh < a.g.nkv; ++kh) unused |= (cnt[kh] == 0);   // a kv head no local q head reads: zero gradient
+    const unsigned grid = (unsigned)(a.g.nq * n_kv_tiles);
+    if (shared || unused) {
+        if (!a.accumulate) {
+            const long long n = (long long)a.g.lc * a.g.nkv * D;
+            hipError_t e = hexi_launch_fill_f32(a.dk, n, 0.f, s);
+            if (e == hipSuccess) e = hexi_launch_fill_f32(a.dv, n, 0.f, s);
+            if (e != hipSuccess) return e;
+        }
+    }
+    if (shared) {
+        bwd_bf16_kernel<true><<<grid, 256, 0, s>>>(a, n_kv_tiles);
+    } else {
+        bwd_bf16_kernel<false><<<grid, 256, 0, s>>>(a, n_kv_tiles);
+    }
     return hipGetLastError();
 }

@@ -68,3 +68,23 @@ __device__ __forceinline__ bf16x8 pack_bf16x8_sum(float a0, float a1, float a2, 
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Direct global->LDS load (LDS DMA): every lane supplies its own global address; the 64 lanes' 16-byte
+// (or 4-byte) pieces land back to back in LDS starting at the wave-uniform byte address `lds_addr`
+// (passed through M0).  Completion is tracked by vmcnt; the caller waits with s_waitcnt vmcnt(0)
+// before the barrier that publishes the data.  Issued through inline assembly so the compiler does
+// not order unrelated LDS reads behind it.
+__device__ __forceinline__ void lds_dma16(const void* gptr, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
+}
+__device__ __forceinline__ void lds_dma4(const void* gptr, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
+}
+
+// fp32 atomic add to global memory without a return value (global_atomic_add_f32)
+__device__ __forceinline__ void global_atomic_add(float* p, float v)
+{
+    __builtin_amdgcn_global_atomic_fadd_f32((float __attribute__((address_space(1)))*)p, v);
+}
