@@ -96,6 +96,8 @@ __global__ void __launch_bounds__(256) bwd_bf16_kernel(const BwdArgs a, const in
             kf[ks] = *reinterpret_cast<const bf16x8*>(k + off + 16 * ks);
             vf[ks] = *reinterpret_cast<const bf16x8*>(v + off + 16 * ks);
         }
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) { pin(kf[ks]); pin(vf[ks]); }
     }
     // K operand fragments of dQ = dS K for this wavefront's 32 output columns d = 32*wave + l32:
     // slot (hh, e) of step u is key 16*u + 8*hh + e, fetched transposed from a staged copy of the

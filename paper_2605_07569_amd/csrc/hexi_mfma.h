@@ -88,3 +88,43 @@ __device__ __forceinline__ void global_atomic_add(float* p, float v)
 {
     __builtin_amdgcn_global_atomic_fadd_f32((float __attribute__((address_space(1)))*)p, v);
 }
+
+// max of three without NaN canonicalisation overhead (scores are finite or -inf)
+__device__ __forceinline__ float max3(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+__device__ __forceinline__ float max2(float a, float b)
+{
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+// max over the two half-waves: lanes l and l^32 end up with max(x[l], x[l^32]) (v_permlane32_swap, no LDS)
+__device__ __forceinline__ float max_across_halves(float x)
+{
+    const unsigned xi = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
+    return max2(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_across_halves(float x)
+{
+    const unsigned xi = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Forces a value that came from an ordinary global load to be complete here.  The direct global->LDS
+// loads above are invisible to the compiler's wait-count bookkeeping; if an ordinary load were
+// still pending when they are issued, the compiler's later "wait until that load is done" would
+// also wait for every LDS DMA issued since.  Pinning the operand fragments before the main loop
+// keeps all such waits out of the loop.
+__device__ __forceinline__ void pin(const bf16x8& x) { asm volatile("" ::"v"(x)); }
+
+// Scheduling hints (one scheduling group each): the next `n` instructions of a class, in order.
+#define HEXI_SCHED_MFMA(n) __builtin_amdgcn_sched_group_barrier(0x008, n, 0)
+#define HEXI_SCHED_DSREAD(n) __builtin_amdgcn_sched_group_barrier(0x100, n, 0)
+#define HEXI_SCHED_DSWRITE(n) __builtin_amdgcn_sched_group_barrier(0x200, n, 0)
+#define HEXI_SCHED_VALU(n) __builtin_amdgcn_sched_group_barrier(0x002, n, 0)
