@@ -1,4 +1,4 @@
-// bf16 backward ring step for gfx950: one workgroup (4 wavefronts, one per SIMD) per
+// bf16 backward ring step, dK / dV part, for gfx950: one workgroup (4 wavefronts, one per SIMD) per
 // (128-key tile, q head).
 //
 // The workgroup keeps its K and V rows in registers as MFMA operands and its dK / dV tiles in
@@ -6,13 +6,15 @@
 // S = Q K^T and dP = dO V^T (keys across lanes, query rows in-lane), P = exp2(S*scale*log2e -
 // LSE*log2e) from the saved global LSE, dS = P (dP - Delta); the accumulator registers holding P
 // and dS are already in operand order for dV += P^T dO and dK += dS^T Q (dO and Q fetched with
-// transposed LDS reads).  dS is written to LDS once (bf16, transposed) and re-read as the A operand
-// of dQ = dS K, which goes out through fp32 atomics.
+// transposed LDS reads).  dQ is produced by a separate q-stationary kernel: adding it from here
+// would need one fp32 atomic per dS K element per key tile, and that atomic traffic (about
+// 3 bytes per kFLOP at 128 keys per workgroup) saturates the L2 atomic units long before the MFMA
+// pipes; recomputing S and dP in the dQ kernel costs 2 extra matmuls out of 5 but keeps every
+// product on the matrix cores.
 //
 // Pipeline: Q / dO tiles are double-buffered in LDS and fetched one tile ahead with direct
-// global->LDS loads; the dQ product of tile t-1 is issued at the start of iteration t, so one
-// barrier per iteration suffices.  LDS tiles are XOR-swizzled (no padding) so that both the 128-bit
-// row reads and the transposed 64-bit reads are bank-conflict free.
+// global->LDS loads, one barrier per tile.  LDS tiles are XOR-swizzled (no padding) so that both the
+// 128-bit row reads and the transposed 64-bit reads are bank-conflict free.
 //
 // The q heads of a GQA group run in different workgroups and add their dK / dV tiles with fp32
 // atomics (plain stores when the group has a single head), so dk/dv must be zero-filled (or hold
@@ -29,21 +31,17 @@ constexpr float LOG2E = 1.4426950408889634f;
 
 // [rows][128] bf16 tile, 16-byte chunk c of row r stored at chunk position c ^ swz_row(r)
 __device__ __forceinline__ int swz_row(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
-// dS^T tile [128 keys][64 q rows] bf16: 8-byte word w (4 consecutive q rows) of key row r at word position
-// w ^ swz_ds(r)
-__device__ __forceinline__ int swz_ds(int r) { const int y = (r >> 1) & 15; return y ^ ((y & 1) << 3); }
 
 struct BwdSmem {
     uint16_t q[2][TM * D];        // 2 x 16 KB
     uint16_t g[2][TM * D];        // dO, 2 x 16 KB
-    uint16_t ds[2][TN * TM];      // dS^T, 2 x 16 KB
     float lse[2][TM];
     float delta[2][TM];
     int qpos[2][TM];
 };
 
 template <bool ATOMIC_DKV>
-__global__ void __launch_bounds__(256) bwd_bf16_kernel(const BwdArgs a, const int n_kv_tiles)
+__global__ void __launch_bounds__(256) bwd_dkdv_bf16_kernel(const BwdArgs a, const int n_kv_tiles)
 {
     const AttnGeom& g = a.g;
     __shared__ __attribute__((aligned(1024))) BwdSmem sm;
@@ -99,30 +97,6 @@ __global__ void __launch_bounds__(256) bwd_bf16_kernel(const BwdArgs a, const in
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) { pin(kf[ks]); pin(vf[ks]); }
     }
-    // K operand fragments of dQ = dS K for this wavefront's 32 output columns d = 32*wave + l32:
-    // slot (hh, e) of step u is key 16*u + 8*hh + e, fetched transposed from a staged copy of the
-    // key tile (staged in the dS / q buffers, which are not in use yet)
-    bf16x8 kq[8];
-    {
-        uint16_t* kst = &sm.q[0][0];    // 128 x 128 bf16 = 32 KB = q[0] and q[1]
-#pragma unroll
-        for (int pass = 0; pass < 8; ++pass) {
-            const int r = (tid >> 4) + 16 * pass, c = tid & 15;
-            const int col = col0 + r < g.lc ? col0 + r : g.lc - 1;
-            *reinterpret_cast<uint4*>(&kst[r * D + ((c ^ swz_row(r)) << 3)]) =
-                *reinterpret_cast<const uint4*>(k + (long long)col * g.kv_stride_tok + c * 8);
-        }
-        __syncthreads();
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int r = 16 * u + 8 * hh + (j16 >> 2);
-            const int c = 4 * wave + 2 * grp2 + ((j16 & 3) >> 1);
-            kq[u] = lds_tr_pair(&kst[r * D + ((c ^ swz_row(r)) << 3) + 4 * (j16 & 1)],
-                                &kst[(r + 4) * D + ((c ^ swz_row(r + 4)) << 3) + 4 * (j16 & 1)]);
-        }
-        __syncthreads();
-    }
-
     f32x16 dk_acc[4], dv_acc[4];
 #pragma unroll
     for (int db = 0; db < 4; ++db)
@@ -177,83 +151,15 @@ __global__ void __launch_bounds__(256) bwd_bf16_kernel(const BwdArgs a, const in
             sm.qpos[buf][lane] = row0 + lane < g.lq ? seg_pos_of_row(g.qs, row0 + lane) : -1;
     };
 
-    // dQ[q][d] of a finished tile from its dS^T in LDS; this wavefront owns d = 32*wave + l32
-    auto dq_tile = [&](int qt, int buf) {
-        const int row0 = qt * TM;
-        f32x16 dq[2];
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) dq[b][r] = 0.f;
-        const uint16_t* ds = &sm.ds[buf][0];
-        auto load_sf = [&](int st) {
-            const int u = st >> 1, b = st & 1;
-            const int r = 16 * u + 8 * hh + (j16 >> 2);
-            const int w = 8 * b + 4 * grp2 + (j16 & 3);
-            return lds_tr_pair(&ds[r * TM + ((w ^ swz_ds(r)) << 2)], &ds[(r + 4) * TM + ((w ^ swz_ds(r + 4)) << 2)]);
-        };
-        constexpr int PF = 4;
-        bf16x8 ring[PF];
-#pragma unroll
-        for (int st = 0; st < PF; ++st) ring[st] = load_sf(st);
-#pragma unroll
-        for (int st = 0; st < 16; ++st) {
-            const bf16x8 sf = ring[st % PF];
-            if (st + PF < 16) ring[st % PF] = load_sf(st + PF);
-            dq[st & 1] = mfma32(sf, kq[st >> 1], dq[st & 1]);
-        }
-        // row i = 32*b + 8*rb + 4*hh + t: the (b, rb, t) part of the address is wave-uniform
-        const long long row_stride = (long long)g.nq * D;
-        float* tile_base = a.dq + ((long long)row0 * g.nq + h) * D;
-        const int lane_off = 4 * hh * g.nq * D + 32 * wave + l32;
-#ifdef EXP_NO_ATOMICS
-        if (g.scale != 12345.f) { if (dq[0][0] + dq[1][5] == 1.2345f) a.dq[0] = 1.f; } else
-#endif
-        if (row0 + TM <= g.lq) {
-#pragma unroll
-            for (int b = 0; b < 2; ++b)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float* rowp = tile_base + (32 * b + 8 * (r >> 2) + (r & 3)) * row_stride;
-                    global_atomic_add(rowp + lane_off, dq[b][r] * g.scale);
-                }
-        } else {
-#pragma unroll
-            for (int b = 0; b < 2; ++b)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int i = 32 * b + 8 * (r >> 2) + 4 * hh + (r & 3);
-                    float* rowp = tile_base + (32 * b + 8 * (r >> 2) + (r & 3)) * row_stride;
-                    if (row0 + i < g.lq) global_atomic_add(rowp + lane_off, dq[b][r] * g.scale);
-                }
-        }
-    };
-
     const int sw_l32 = swz_row(l32);
-    // The q tiles are visited in rotated order, each key tile starting at a different q tile, so
-    // that workgroups running side by side do not add into the same dQ rows at the same moment.
-    const int n_it = n_qtiles - qt_begin;
-#ifndef EXP_STAGGER
-#define EXP_STAGGER 0
-#endif
-    const int rot = n_it > 0 ? (int)(((long long)kv_tile * EXP_STAGGER) % n_it) : 0;
-    auto tile_of = [&](int it) { int t = it + rot; if (t >= n_it) t -= n_it; return qt_begin + t; };
-    if (n_it > 0) fetch_tile(tile_of(0), 0);
-    for (int it = 0; it < n_it; ++it) {
-        const int qt = tile_of(it);
-        const int buf = it & 1;
+    if (qt_begin < n_qtiles) fetch_tile(qt_begin, 0);
+    for (int qt = qt_begin; qt < n_qtiles; ++qt) {
+        const int buf = (qt - qt_begin) & 1;
         const bool partial = qt < qt_full || qt * TM + TM > g.lq;
         // publish tile qt: wait for this wavefront's outstanding global->LDS loads, then barrier
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-#ifdef EXP_NO_FETCH
-        if (it + 1 < n_it && g.scale == 12345.f) fetch_tile(tile_of(it + 1), buf ^ 1);
-#else
-        if (it + 1 < n_it) fetch_tile(tile_of(it + 1), buf ^ 1);
-#endif
-#ifndef EXP_NO_DQ
-        if (it > 0) dq_tile(tile_of(it - 1), buf ^ 1);
-#endif
+        if (qt + 1 < n_qtiles) fetch_tile(qt + 1, buf ^ 1);
 
         const uint16_t* Qs = &sm.q[buf][0];
         const uint16_t* Gs = &sm.g[buf][0];
@@ -300,22 +206,6 @@ __global__ void __launch_bounds__(256) bwd_bf16_kernel(const BwdArgs a, const in
                     dp[b][4 * rb + t] = p * (dp[b][4 * rb + t] - d4[t]);
                 }
             }
-        // dS^T to LDS for the dQ product of the next iteration: key row, word = 4 consecutive q rows
-        {
-            uint16_t* ds = &sm.ds[buf][0];
-            const int r = 32 * wave + l32;
-            const int sw = swz_ds(r);
-#pragma unroll
-            for (int b = 0; b < 2; ++b)
-#pragma unroll
-                for (int rb = 0; rb < 4; ++rb) {
-                    bf16x4 w4;
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) w4[t] = (__bf16)dp[b][4 * rb + t];
-                    const int w = 8 * b + 2 * rb + hh;
-                    *reinterpret_cast<bf16x4*>(&ds[r * TM + ((w ^ sw) << 2)]) = w4;
-                }
-        }
         // dV += P^T dO, dK += dS^T Q over four 16-row steps x four 32-column blocks
         {
             bf16x8 pf[4], df[4];
@@ -340,11 +230,7 @@ __global__ void __launch_bounds__(256) bwd_bf16_kernel(const BwdArgs a, const in
                 qr[st] = lds_tr_pair(&Qs[tr_off(st, 0)], &Qs[tr_off(st, 1)]);
             }
 #pragma unroll
-#ifdef EXP_NO_DVDK
-            for (int st = 0; st < (g.scale == 12345.f ? 16 : 0); ++st) {
-#else
             for (int st = 0; st < 16; ++st) {
-#endif
                 const bf16x8 gf = gr[st % PF], qf = qr[st % PF];
                 if (st + PF < 16) {
                     gr[st % PF] = lds_tr_pair(&Gs[tr_off(st + PF, 0)], &Gs[tr_off(st + PF, 1)]);
@@ -355,11 +241,6 @@ __global__ void __launch_bounds__(256) bwd_bf16_kernel(const BwdArgs a, const in
             }
         }
     }
-    if (n_it > 0) {
-        __syncthreads();
-        dq_tile(tile_of(n_it - 1), (n_it - 1) & 1);
-    }
-
     // dK / dV: lane holds column d = 32*db + l32; register r holds key 32*wave + 8*(r/4) + 4*hh + r%4
 #pragma unroll
     for (int db = 0; db < 4; ++db)
@@ -401,9 +282,11 @@ hipError_t hexi_launch_bwd_bf16(const BwdArgs& a, hipStream_t s)
         }
     }
     if (shared) {
-        bwd_bf16_kernel<true><<<grid, 256, 0, s>>>(a, n_kv_tiles);
+        bwd_dkdv_bf16_kernel<true><<<grid, 256, 0, s>>>(a, n_kv_tiles);
     } else {
-        bwd_bf16_kernel<false><<<grid, 256, 0, s>>>(a, n_kv_tiles);
+        bwd_dkdv_bf16_kernel<false><<<grid, 256, 0, s>>>(a, n_kv_tiles);
     }
-    return hipGetLastError();
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return hexi_launch_bwd_dq_bf16(a, s);
 }

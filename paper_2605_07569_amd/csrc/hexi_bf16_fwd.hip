@@ -35,6 +35,9 @@ struct FwdSmem {
     uint16_t k[2][TN * D];   // 2 x 16 KB
     uint16_t v[2][TN * D];   // 2 x 16 KB
     int kpos[2][TN];
+#ifdef EXP_BIG_LDS
+    int pad[12000];
+#endif
 };
 
 __global__ void __launch_bounds__(256, 2) fwd_bf16_kernel(const FwdArgs a, const int n_q_tiles)
@@ -135,14 +138,22 @@ __global__ void __launch_bounds__(256, 2) fwd_bf16_kernel(const FwdArgs a, const
     const int sw_l32 = swz_row(l32);
     const int jj = j16 >> 2, cl = 2 * grp2 + ((j16 & 3) >> 1);
 
+#ifdef EXP_TIMING
+    long long tacc[6] = {0, 0, 0, 0, 0, 0}; long long t0 = __builtin_amdgcn_s_memtime(), t1;
+#define TICK(i) { t1 = __builtin_amdgcn_s_memtime(); tacc[i] += t1 - t0; t0 = t1; }
+#else
+#define TICK(i)
+#endif
     if (n_tiles > 0) fetch_tile(0, 0);
     for (int tile = 0; tile < n_tiles; ++tile) {
         const int buf = tile & 1;
         const bool partial = tile >= n_full_tiles;
         // publish tile: wait for this wavefront's outstanding global->LDS loads, then barrier
+        TICK(0)
 #ifndef EXP_NO_VMWAIT
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #endif
+        TICK(1)
 #ifndef EXP_NO_BARRIER
         __syncthreads();
 #endif
@@ -152,6 +163,7 @@ __global__ void __launch_bounds__(256, 2) fwd_bf16_kernel(const FwdArgs a, const
         if (tile + 1 < n_tiles) fetch_tile(tile + 1, buf ^ 1);
 #endif
 
+        TICK(2)
         const uint16_t* Ks = &sm.k[buf][0];
         const uint16_t* Vs = &sm.v[buf][0];
         // S^T[key][q] for two 32-key blocks, LDS reads running ahead of the MFMAs
@@ -180,6 +192,10 @@ __global__ void __launch_bounds__(256, 2) fwd_bf16_kernel(const FwdArgs a, const
                 if (st + PF < 16) HEXI_SCHED_DSREAD(1);
             }
         }
+#ifdef EXP_TIMING
+        asm volatile("s_nop 0" :: "v"(s[0][0]), "v"(s[1][15]));
+#endif
+        TICK(3)
         // first V^T fragments can be on their way while the softmax runs
         auto v_off = [&](int st, int second) {
             const int u = st >> 2, db = st & 3;
@@ -192,6 +208,10 @@ __global__ void __launch_bounds__(256, 2) fwd_bf16_kernel(const FwdArgs a, const
 #pragma unroll
         for (int st = 0; st < PFV; ++st) vr[st] = lds_tr_pair(&Vs[v_off(st, 0)], &Vs[v_off(st, 1)]);
 
+#ifdef EXP_NO_SMAX
+        bf16x8 pf[4];
+        for (int u = 0; u < 4; ++u) { f32x4 t = {s[u >> 1][(u & 1) * 8], s[u >> 1][(u & 1) * 8 + 1], s[u >> 1][(u & 1) * 8 + 2], s[u >> 1][(u & 1) * 8 + 3]}; pf[u] = __builtin_bit_cast(bf16x8, t); }
+#else
         if (partial) {
 #pragma unroll
             for (int b = 0; b < 2; ++b)
@@ -244,12 +264,21 @@ __global__ void __launch_bounds__(256, 2) fwd_bf16_kernel(const FwdArgs a, const
         l_run += ps;       // per-half partial sums; the two halves are added at the end
         lr_run += psr;
 
+#endif
+#ifdef EXP_TIMING
+        asm volatile("s_nop 0" :: "v"(pf[3]));
+#endif
+        TICK(4)
         // O^T[d][q] += V^T P^T over four 16-key steps x four 32-column blocks
 #pragma unroll
         for (int st = 0; st < 16; ++st) {
             const bf16x8 vf = vr[st % PFV];
             if (st + PFV < 16) vr[st % PFV] = lds_tr_pair(&Vs[v_off(st + PFV, 0)], &Vs[v_off(st + PFV, 1)]);
+#ifndef EXP_NO_PV
             oacc[st & 3] = mfma32(vf, pf[st >> 2], oacc[st & 3]);
+#else
+            if (st == 0) oacc[0] = mfma32(vf, pf[0], oacc[0]); if (st == 1) oacc[1] = mfma32(vf, pf[1], oacc[1]); if (st == 2) oacc[2] = mfma32(vf, pf[2], oacc[2]); if (st == 3) oacc[3] = mfma32(vf, pf[3], oacc[3]);
+#endif
         }
 #pragma unroll
         for (int st = 0; st < 16; ++st) {
@@ -258,6 +287,12 @@ __global__ void __launch_bounds__(256, 2) fwd_bf16_kernel(const FwdArgs a, const
         }
     }
 
+#ifdef EXP_TIMING
+    asm volatile("s_nop 0" :: "v"(oacc[0][0]), "v"(oacc[3][15]));
+    TICK(0)
+    if (tid == 0) { for (int i = 0; i < 6; ++i) a.o[(long long)unit * 8 + i] = (float)tacc[i]; a.o[(long long)unit * 8 + 6] = (float)n_tiles; }
+    return;
+#endif
     const float l_tot = sum_across_halves(l_run);
     const float lr_tot = sum_across_halves(lr_run);
     float inv = 0.f, lse_new = -INFINITY;

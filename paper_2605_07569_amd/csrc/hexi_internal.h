@@ -65,7 +65,8 @@ struct BwdArgs {
 hipError_t hexi_launch_fwd_f32(const FwdArgs& a, hipStream_t s);
 hipError_t hexi_launch_bwd_f32(const BwdArgs& a, hipStream_t s);
 hipError_t hexi_launch_fwd_bf16(const FwdArgs& a, hipStream_t s);
-hipError_t hexi_launch_bwd_bf16(const BwdArgs& a, hipStream_t s);
+hipError_t hexi_launch_bwd_bf16(const BwdArgs& a, hipStream_t s);      // dK/dV kernel, then the dQ kernel
+hipError_t hexi_launch_bwd_dq_bf16(const BwdArgs& a, hipStream_t s);
 hipError_t hexi_launch_merge(long long n_rows, int nq, int d, float* o_acc, float* lse_acc, const float* o_part,
                              const float* lse_part, void* o_final, int o_final_dtype, hipStream_t s);
 hipError_t hexi_launch_delta(long long lq, int nq, int d, const float* o, const void* d_o, int dtype,
