@@ -70,11 +70,15 @@ def main():
         run.dq.zero_()
         for j, ch in enumerate(w.chunks):
             flags = hexi.HEXI_COMPUTE_DELTA if j == 0 else 0
+            # the step's two kernels are issued through the two halves of the call so that HIP events on the
+            # launch stream bracket the dominant one (dK/dV) alone; same launches, same order as one call
             ka, kb = ev(), ev()
             ka.record()
             hexi.hexi_attn_bwd_chunk(run.desc[j], w.q_segs, ch, run.q, run.k[j], run.v[j], run.o, run.d_o,
-                                     run.lse, run.delta, run.dq, run.dk[j], run.dv[j], flags=flags)
+                                     run.lse, run.delta, None, run.dk[j], run.dv[j], flags=flags | hexi.HEXI_SKIP_DQ)
             kb.record()
+            hexi.hexi_attn_bwd_chunk(run.desc[j], w.q_segs, ch, run.q, run.k[j], run.v[j], run.o, run.d_o,
+                                     run.lse, run.delta, run.dq, None, None, flags=hexi.HEXI_SKIP_DKDV)
             if j in live and j != 0:
                 kern_ev.append((j, ka, kb))
         e2.record()
@@ -88,16 +92,18 @@ def main():
     bwd_ms = sum(a.elapsed_time(b) for a, b in bwd_ev) / args.steps
     tflops = (flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12
 
-    # dominant kernel: bf16 backward.  Per launch: algorithmic flops = 10*d*nq*(pairs of that chunk).
+    # dominant kernel: the dK/dV half of the backward step.  Per launch its algorithmic work is the four
+    # matmuls S = QK^T, dP = dO V^T, dV = P^T dO, dK = dS^T Q on the unmasked pairs: 8*d*nq*(pairs of that chunk).
+    # (With GQA the event pair also covers the two zero-fills of dk/dv that precede the kernel.)
     if kern_ev:
         k_ms = sum(a.elapsed_time(b) for _, a, b in kern_ev) / len(kern_ev)
-        k_flops = sum(10.0 * d * nq * n_pairs_chunk[j] for j, _, _ in kern_ev) / len(kern_ev)
+        k_flops = sum(8.0 * d * nq * n_pairs_chunk[j] for j, _, _ in kern_ev) / len(kern_ev)
     else:  # single live chunk: fall back to the whole backward replay
         k_ms, k_flops = bwd_ms, flops_bwd
     achieved = k_flops / (k_ms * 1e-3) / 1e12
     is_bf16 = w.dtype == "bf16"
     peak = PEAK_BF16_TFLOPS if is_bf16 else 157.3
-    roofline = {"bound": "mfma" if is_bf16 else "alu", "kernel": "bwd_bf16_kernel" if is_bf16 else "bwd_f32_kernel",
+    roofline = {"bound": "mfma" if is_bf16 else "alu", "kernel": "bwd_dkdv_bf16_kernel" if is_bf16 else "bwd_f32_kernel",
                 "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                 "traffic": MEASURED_TRAFFIC_BYTES.get(w.name), "launch_ms": round(k_ms, 4),
                 "flops_per_launch": k_flops}

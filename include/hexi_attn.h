@@ -51,6 +51,8 @@ extern "C" {
 #define HEXI_ACCUMULATE     1u  /* fwd: merge the chunk's result into o/lse in place (fused LSE merge);
                                    bwd: dk/dv += instead of = */
 #define HEXI_COMPUTE_DELTA  2u  /* bwd: first fill delta = rowsum(d_o * o) from the merged o */
+#define HEXI_SKIP_DQ        4u  /* bwd: produce only dk/dv (dq_acc is not touched and may be NULL) */
+#define HEXI_SKIP_DKDV      8u  /* bwd: produce only dq (dk/dv are not touched and may be NULL) */
 
 #define HEXI_TILE_EMPTY   0
 #define HEXI_TILE_FULL    1
@@ -126,9 +128,13 @@ int hexi_attn_merge_lse(int64_t n_rows, int32_t n_q_heads, int32_t head_dim,
  *   dK_j = scale sum_{h in group} sum_i dS_ij q_i.
  * o is the merged fp32 forward output and is read only under HEXI_COMPUTE_DELTA (which fills
  * delta for the whole shard before the chunk is processed); otherwise delta is an input.
- * dq_acc (fp32) accumulates over calls: the caller zeroes it before the first chunk.  The adds into
- * dq_acc are floating-point atomics, so their order (and the last bits) can vary between runs.
- * dk, dv (fp32, this chunk's rows) are overwritten, or added to under HEXI_ACCUMULATE.  A chunk
+ * dq_acc (fp32) accumulates over calls: the caller zeroes it before the first chunk.  Each dq row is
+ * updated by one workgroup per call in a fixed order (bf16 path), so dq is reproducible run to run.
+ * dk, dv (fp32, this chunk's rows) are overwritten, or added to under HEXI_ACCUMULATE; when several
+ * local q heads share a kv head their contributions are summed with floating-point atomics, whose
+ * order (and so the last bits of dk/dv) can vary between runs.  HEXI_SKIP_DQ / HEXI_SKIP_DKDV
+ * restrict the call to one of the two halves (they are separate kernels and may be issued on
+ * different streams); both set is HEXI_EINVAL.  A chunk
  * wholly in the shard's future writes zeros to dk/dv (nothing under HEXI_ACCUMULATE) and leaves
  * dq_acc untouched.  d_o has the dtype and strides of q.
  */

@@ -191,21 +191,27 @@ HEXI_EXPORT int hexi_attn_bwd_chunk(const hexi_attn_desc* desc, const hexi_range
     BwdArgs a;
     int rc = build_geom(desc, q_range, kv_range, &a.g);
     if (rc != HEXI_OK) return rc;
-    if (!q || !k || !v || !d_o || !lse || !delta || !dq_acc || !dk || !dv) return fail(HEXI_EINVAL, "null tensor pointer");
-    if (flags & ~(HEXI_ACCUMULATE | HEXI_COMPUTE_DELTA)) return fail(HEXI_EINVAL, "unknown flag bits 0x%x", flags);
+    if (flags & ~(HEXI_ACCUMULATE | HEXI_COMPUTE_DELTA | HEXI_SKIP_DQ | HEXI_SKIP_DKDV)) return fail(HEXI_EINVAL, "unknown flag bits 0x%x", flags);
+    const bool want_dq = !(flags & HEXI_SKIP_DQ), want_dkdv = !(flags & HEXI_SKIP_DKDV);
+    if (!want_dq && !want_dkdv) return fail(HEXI_EINVAL, "HEXI_SKIP_DQ and HEXI_SKIP_DKDV are both set");
+    if (!q || !k || !v || !d_o || !lse || !delta || (want_dq && !dq_acc) || (want_dkdv && (!dk || !dv)))
+        return fail(HEXI_EINVAL, "null tensor pointer");
     if ((flags & HEXI_COMPUTE_DELTA) && !o) return fail(HEXI_EINVAL, "HEXI_COMPUTE_DELTA needs o");
-    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(dq_acc) || !aligned16(dk) || !aligned16(dv) ||
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || (want_dq && !aligned16(dq_acc)) ||
+        (want_dkdv && (!aligned16(dk) || !aligned16(dv))) ||
         ((flags & HEXI_COMPUTE_DELTA) && !aligned16(o)))
         return fail(HEXI_EALIGN, "tensor base pointers must be 16-byte aligned");
     hipStream_t s = (hipStream_t)hip_stream;
     a.q = q; a.k = k; a.v = v; a.d_o = d_o; a.lse = lse; a.delta = delta; a.dq = dq_acc; a.dk = dk; a.dv = dv;
     a.accumulate = (flags & HEXI_ACCUMULATE) ? 1 : 0;
+    a.want_dq = want_dq ? 1 : 0;
+    a.want_dkdv = want_dkdv ? 1 : 0;
     hipError_t e = hipSuccess;
     if (flags & HEXI_COMPUTE_DELTA)
         e = hexi_launch_delta(a.g.lq, a.g.nq, a.g.d, o, d_o, desc->dtype, a.g.q_stride_tok, a.g.q_stride_head, delta, s);
     if (e == hipSuccess) {
         if (chunk_in_future(a.g)) {
-            if (!a.accumulate) {
+            if (!a.accumulate && want_dkdv) {
                 const long long n = (long long)a.g.lc * a.g.nkv * a.g.d;
                 e = hexi_launch_fill_f32(dk, n, 0.f, s);
                 if (e == hipSuccess) e = hexi_launch_fill_f32(dv, n, 0.f, s);

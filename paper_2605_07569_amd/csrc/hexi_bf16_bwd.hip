@@ -266,27 +266,24 @@ __global__ void __launch_bounds__(256) bwd_dkdv_bf16_kernel(const BwdArgs a, con
 
 hipError_t hexi_launch_bwd_bf16(const BwdArgs& a, hipStream_t s)
 {
-    const int n_kv_tiles = (a.g.lc + TN - 1) / TN;
-    // does any kv head serve more than one q head?  then the heads' dK/dV tiles are summed atomically
-    int cnt[HEXI_MAX_HEADS] = {0};
-    bool shared = false, unused = false;
-    for (int h = 0; h < a.g.nq; ++h) shared |= (++cnt[a.g.kv_of_q[h]] > 1);
-    for (int kh = 0; kh < a.g.nkv; ++kh) unused |= (cnt[kh] == 0);   // a kv head no local q head reads: zero gradient
-    const unsigned grid = (unsigned)(a.g.nq * n_kv_tiles);
-    if (shared || unused) {
-        if (!a.accumulate) {
+    if (a.want_dkdv) {
+        const int n_kv_tiles = (a.g.lc + TN - 1) / TN;
+        // does any kv head serve more than one q head?  then the heads' dK/dV tiles are summed atomically
+        int cnt[HEXI_MAX_HEADS] = {0};
+        bool shared = false, unused = false;
+        for (int h = 0; h < a.g.nq; ++h) shared |= (++cnt[a.g.kv_of_q[h]] > 1);
+        for (int kh = 0; kh < a.g.nkv; ++kh) unused |= (cnt[kh] == 0);   // a kv head no local q head reads: zero gradient
+        const unsigned grid = (unsigned)(a.g.nq * n_kv_tiles);
+        if ((shared || unused) && !a.accumulate) {
             const long long n = (long long)a.g.lc * a.g.nkv * D;
             hipError_t e = hexi_launch_fill_f32(a.dk, n, 0.f, s);
             if (e == hipSuccess) e = hexi_launch_fill_f32(a.dv, n, 0.f, s);
             if (e != hipSuccess) return e;
         }
+        if (shared) bwd_dkdv_bf16_kernel<true><<<grid, 256, 0, s>>>(a, n_kv_tiles);
+        else bwd_dkdv_bf16_kernel<false><<<grid, 256, 0, s>>>(a, n_kv_tiles);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
     }
-    if (shared) {
-        bwd_dkdv_bf16_kernel<true><<<grid, 256, 0, s>>>(a, n_kv_tiles);
-    } else {
-        bwd_dkdv_bf16_kernel<false><<<grid, 256, 0, s>>>(a, n_kv_tiles);
-    }
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    return hexi_launch_bwd_dq_bf16(a, s);
+    return a.want_dq ? hexi_launch_bwd_dq_bf16(a, s) : hipSuccess;
 }

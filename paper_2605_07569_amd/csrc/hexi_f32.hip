@@ -272,14 +272,14 @@ __global__ void __launch_bounds__(256) bwd_f32_kernel(const BwdArgs a)
 #pragma unroll
                 for (int c = 0; c < DQ; ++c) dq[c] = fmaf(ds, Ks[j][c8 * DQ + c], dq[c]);
             }
-            if (row0 + i_own < g.lq) {
+            if (a.want_dq && row0 + i_own < g.lq) {
                 float* dqp = a.dq + ((long long)(row0 + i_own) * g.nq + h) * D + c8 * DQ;
 #pragma unroll
                 for (int c = 0; c < DQ; ++c) unsafeAtomicAdd(dqp + c, dq[c] * g.scale);
             }
         }
     }
-    if (col0 + j_own < g.lc) {
+    if (a.want_dkdv && col0 + j_own < g.lc) {
         float* dkp = a.dk + ((long long)(col0 + j_own) * g.nkv + kvh) * D + c4 * DS;
         float* dvp = a.dv + ((long long)(col0 + j_own) * g.nkv + kvh) * D + c4 * DS;
 #pragma unroll

@@ -59,6 +59,7 @@ struct BwdArgs {
     const float *lse, *delta;
     float *dq, *dk, *dv;
     int accumulate;
+    int want_dq, want_dkdv;   // which halves of the backward step to run
 };
 
 // Launchers (each returns a hipError_t from the launch).

@@ -14,7 +14,7 @@ import numpy as np
 HEXI_OK = 0
 HEXI_EINVAL, HEXI_EUNSUPPORTED, HEXI_EALIGN, HEXI_EWORKSPACE, HEXI_EHIP = -1, -2, -3, -4, -5
 HEXI_BF16, HEXI_F32 = 0, 1
-HEXI_ACCUMULATE, HEXI_COMPUTE_DELTA = 1, 2
+HEXI_ACCUMULATE, HEXI_COMPUTE_DELTA, HEXI_SKIP_DQ, HEXI_SKIP_DKDV = 1, 2, 4, 8
 HEXI_TILE_EMPTY, HEXI_TILE_FULL, HEXI_TILE_PARTIAL = 0, 1, 2
 HEXI_MAX_SEGS = 16
 

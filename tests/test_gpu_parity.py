@@ -191,6 +191,37 @@ def test_future_chunk_and_merge_outputs():
             assert torch.equal(fin, oa.to(torch.bfloat16))
 
 
+def test_backward_halves_and_dq_reproducible():
+    # HEXI_SKIP_DQ / HEXI_SKIP_DKDV run the two halves of the step separately; together they equal the full
+    # call.  dq (bf16 path) has a fixed summation order: bit-identical between runs.
+    w = wl.config(3, shrink=32)
+    inputs = wl.make_inputs(w)
+    run = replay.ShardRun(w, inputs, DEV)
+    run.step(); torch.cuda.synchronize()
+    dq_full = run.dq.clone()
+    dk_full = [x.clone() for x in run.dk]
+    run.dq.zero_()
+    for j, ch in enumerate(w.chunks):
+        run.dk[j].fill_(7.0); run.dv[j].fill_(7.0)
+        hexi.hexi_attn_bwd_chunk(run.desc[j], w.q_segs, ch, run.q, run.k[j], run.v[j], run.o, run.d_o, run.lse, run.delta,
+                                 run.dq, None, None, flags=hexi.HEXI_SKIP_DKDV)
+    torch.cuda.synchronize()
+    assert torch.equal(run.dq, dq_full)
+    assert all(torch.all(x == 7.0) for x in run.dk)
+    dq_before = run.dq.clone()
+    for j, ch in enumerate(w.chunks):
+        hexi.hexi_attn_bwd_chunk(run.desc[j], w.q_segs, ch, run.q, run.k[j], run.v[j], run.o, run.d_o, run.lse, run.delta,
+                                 None, run.dk[j], run.dv[j], flags=hexi.HEXI_SKIP_DQ)
+    torch.cuda.synchronize()
+    assert torch.equal(run.dq, dq_before)
+    for a, b in zip(run.dk, dk_full):
+        assert torch.allclose(a, b, rtol=1e-4, atol=1e-5)
+    with pytest.raises(hexi.HexiError) as e:
+        hexi.hexi_attn_bwd_chunk(run.desc[0], w.q_segs, w.chunks[0], run.q, run.k[0], run.v[0], run.o, run.d_o, run.lse,
+                                 run.delta, run.dq, run.dk[0], run.dv[0], flags=hexi.HEXI_SKIP_DQ | hexi.HEXI_SKIP_DKDV)
+    assert e.value.code == hexi.HEXI_EINVAL
+
+
 def test_forward_is_deterministic():
     w = wl.config(3, shrink=32)
     inputs = wl.make_inputs(w)
