@@ -19,7 +19,7 @@ import torch
 PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16 MFMA peak: 256 CU x 2.4 GHz x 4096 flop/clk/CU
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # command (see profiles/); None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {"cfg2_3b_zigzag": 1.014e9}   # bwd_dkdv_bf16_kernel: 611 MB fetched + 403 MB written
 
 
 def parse():
@@ -29,6 +29,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", type=int, default=2, help="shard configuration 1..5 (default 2: the 3B-like zigzag shard)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (a kernel of known HBM traffic) before the timed "
+                         "region, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows per q segment for the oracle sample (0: auto)")
     return ap.parse_args()
 
@@ -57,6 +60,12 @@ def main():
     for _ in range(args.warmup):
         run.step()
     torch.cuda.synchronize()
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").fill_(1.0)   # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
     fwd_ev, bwd_ev, kern_ev = [], [], []
