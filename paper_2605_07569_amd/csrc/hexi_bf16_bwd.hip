@@ -21,6 +21,7 @@
 // the running sum under HEXI_ACCUMULATE) before the launch.
 #include "hexi_internal.h"
 #include "hexi_mfma.h"
+#include <type_traits>
 
 namespace {
 
@@ -152,93 +153,139 @@ __global__ void __launch_bounds__(256) bwd_dkdv_bf16_kernel(const BwdArgs a, con
     };
 
     const int sw_l32 = swz_row(l32);
-    if (qt_begin < n_qtiles) fetch_tile(qt_begin, 0);
-    for (int qt = qt_begin; qt < n_qtiles; ++qt) {
-        const int buf = (qt - qt_begin) & 1;
-        const bool partial = qt < qt_full || qt * TM + TM > g.lq;
-        // publish tile qt: wait for this wavefront's outstanding global->LDS loads, then barrier
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (qt + 1 < n_qtiles) fetch_tile(qt + 1, buf ^ 1);
+    const int jj = j16 >> 2, cl = 2 * grp2 + ((j16 & 3) >> 1);
 
+    // One q tile.  The two 32-row q blocks are staggered so that the VALU work of one block sits
+    // between MFMAs of the other in program order (the matrix pipe keeps running under the VALU):
+    //   A: S/dP(block 0) | B: S/dP(block 1) + VALU(block 0) | C: dV/dK(block 0) + VALU(block 1) | D: dV/dK(block 1)
+    // Each step (2 MFMAs, their LDS prefetches, 2 elements of VALU work) ends in a scheduling barrier,
+    // so the hand-written interleave is what gets issued.  MASKED is a compile-time flag: masked tiles
+    // take a copy of the body with selects, unmasked ones carry no per-element masking at all.
+    auto tile_body = [&](int buf, auto masked_c) __attribute__((always_inline)) {
+        constexpr bool MASKED = decltype(masked_c)::value;
         const uint16_t* Qs = &sm.q[buf][0];
         const uint16_t* Gs = &sm.g[buf][0];
-        // S[q][key] and dP[q][key]: two 32-row q blocks, this wavefront's 32 keys
         f32x16 s[2], dp[2];
+        bf16x8 pf[4], df[4];
+        f32x4 lse4[2][4], del4[2][4];     // per-row constants of the rows this lane holds: i = 32*b + 8*rb + 4*hh + t
+        constexpr int PF = 3;             // LDS fragments requested this many steps ahead of their MFMA
+        bf16x8 ra[PF], rb_[PF];
+
+        auto nat_off = [&](int b, int ks) { return (32 * b + l32) * D + (((2 * ks + hh) ^ sw_l32) << 3); };
+        auto tr_off = [&](int b, int st, int second) {
+            const int u = 2 * b + (st >> 2), db = st & 3;
+            const int r = 16 * u + 4 * hh + jj + 8 * second;
+            const int pos = (((db ^ jj) << 2) | (cl ^ (hh + 2 * second)));
+            return r * D + (pos << 3) + 4 * (j16 & 1);
+        };
+        auto load_nat = [&](int b, int ks, int slot) {
+            ra[slot] = *reinterpret_cast<const bf16x8*>(&Qs[nat_off(b, ks)]);
+            rb_[slot] = *reinterpret_cast<const bf16x8*>(&Gs[nat_off(b, ks)]);
+        };
+        auto load_tr = [&](int b, int st, int slot) {
+            ra[slot] = lds_tr_pair(&Gs[tr_off(b, st, 0)], &Gs[tr_off(b, st, 1)]);
+            rb_[slot] = lds_tr_pair(&Qs[tr_off(b, st, 0)], &Qs[tr_off(b, st, 1)]);
+        };
+        // P and dS of elements e, e+1 of q block b.  Rows whose LSE is -inf see nothing anywhere, so they
+        // are masked in every tile they appear in.
+        auto valu2 = [&](int b, int e) {
+#pragma unroll
+            for (int x = e; x < e + 2; ++x) {
+                const int rb = x >> 2, t = x & 3;
+                float p = fast_exp2(fmaf(s[b][x], scale_log2, lse4[b][rb][t]));
+                if (MASKED) p = (my_kpos > sm.qpos[buf][32 * b + 8 * rb + 4 * hh + t]) ? 0.f : p;
+                s[b][x] = p;
+                dp[b][x] = p * (dp[b][x] - del4[b][rb][t]);
+            }
+        };
+        auto pack = [&](int b, int half) {
+            const int x = 8 * half;
+            pf[2 * b + half] = pack_bf16x8(s[b][x], s[b][x + 1], s[b][x + 2], s[b][x + 3], s[b][x + 4], s[b][x + 5], s[b][x + 6], s[b][x + 7]);
+            df[2 * b + half] = pack_bf16x8(dp[b][x], dp[b][x + 1], dp[b][x + 2], dp[b][x + 3], dp[b][x + 4], dp[b][x + 5], dp[b][x + 6], dp[b][x + 7]);
+        };
+
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) { s[b][r] = 0.f; dp[b][r] = 0.f; }
-        {
-            auto frag_off = [&](int st) { return (32 * (st & 1) + l32) * D + (((2 * (st >> 1) + hh) ^ sw_l32) << 3); };
-            constexpr int PF = 3;
-            bf16x8 qr[PF], gr[PF];
+        // phase A: S/dP of block 0; the row constants are fetched alongside
 #pragma unroll
-            for (int st = 0; st < PF; ++st) {
-                qr[st] = *reinterpret_cast<const bf16x8*>(&Qs[frag_off(st)]);
-                gr[st] = *reinterpret_cast<const bf16x8*>(&Gs[frag_off(st)]);
-            }
+        for (int ks = 0; ks < PF; ++ks) load_nat(0, ks, ks);
 #pragma unroll
-            for (int st = 0; st < 16; ++st) {
-                const bf16x8 qa = qr[st % PF], ga = gr[st % PF];
-                if (st + PF < 16) {
-                    qr[st % PF] = *reinterpret_cast<const bf16x8*>(&Qs[frag_off(st + PF)]);
-                    gr[st % PF] = *reinterpret_cast<const bf16x8*>(&Gs[frag_off(st + PF)]);
-                }
-                s[st & 1] = mfma32(qa, kf[st >> 1], s[st & 1]);
-                dp[st & 1] = mfma32(ga, vf[st >> 1], dp[st & 1]);
+        for (int ks = 0; ks < 8; ++ks) {
+            const bf16x8 qa = ra[ks % PF], ga = rb_[ks % PF];      // ring slot = (global step) % PF
+            if (ks + PF < 8) load_nat(0, ks + PF, ks % PF);
+            else load_nat(1, ks + PF - 8, ks % PF);
+            {
+                const int b = ks >> 2, rb = ks & 3;
+                const f32x4 l = *reinterpret_cast<const f32x4*>(&sm.lse[buf][32 * b + 8 * rb + 4 * hh]);
+                lse4[b][rb] = f32x4{-LOG2E * l[0], -LOG2E * l[1], -LOG2E * l[2], -LOG2E * l[3]};
+                del4[b][rb] = *reinterpret_cast<const f32x4*>(&sm.delta[buf][32 * b + 8 * rb + 4 * hh]);
             }
+            s[0] = mfma32(qa, kf[ks], s[0]);
+            dp[0] = mfma32(ga, vf[ks], dp[0]);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        // P and dS in place (s <- P, dp <- dS); in-lane row index i = 32*b + 8*rb + 4*hh + t.
-        // Rows whose LSE is -inf see nothing anywhere, so they are masked in every tile they appear in.
+        // phase B: S/dP of block 1, VALU of block 0
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int ks = 0; ks < 8; ++ks) {
+            const bf16x8 qa = ra[(8 + ks) % PF], ga = rb_[(8 + ks) % PF];
+            if (ks + PF < 8) load_nat(1, ks + PF, (8 + ks) % PF);
+            else load_tr(0, ks + PF - 8, (8 + ks) % PF);
+            s[1] = mfma32(qa, kf[ks], s[1]);
+            dp[1] = mfma32(ga, vf[ks], dp[1]);
+            valu2(0, 2 * ks);
+            if (ks == 4) pack(0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        pack(0, 1);
+        // phase C: dV/dK of block 0, VALU of block 1
 #pragma unroll
-            for (int rb = 0; rb < 4; ++rb) {
-                const int i0 = 32 * b + 8 * rb + 4 * hh;
-                const f32x4 l4 = *reinterpret_cast<const f32x4*>(&sm.lse[buf][i0]);
-                const f32x4 d4 = *reinterpret_cast<const f32x4*>(&sm.delta[buf][i0]);
+        for (int st = 0; st < 8; ++st) {
+            const bf16x8 gf = ra[(16 + st) % PF], qf = rb_[(16 + st) % PF];
+            if (st + PF < 8) load_tr(0, st + PF, (16 + st) % PF);
+            else load_tr(1, st + PF - 8, (16 + st) % PF);
+            dv_acc[st & 3] = mfma32(pf[st >> 2], gf, dv_acc[st & 3]);
+            dk_acc[st & 3] = mfma32(df[st >> 2], qf, dk_acc[st & 3]);
+            valu2(1, 2 * st);
+            if (st == 4) pack(1, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        pack(1, 1);
+        // phase D: dV/dK of block 1
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    float p = fast_exp2(s[b][4 * rb + t] * scale_log2 - l4[t] * LOG2E);
-                    if (partial && my_kpos > sm.qpos[buf][i0 + t]) p = 0.f;
-                    s[b][4 * rb + t] = p;
-                    dp[b][4 * rb + t] = p * (dp[b][4 * rb + t] - d4[t]);
-                }
-            }
-        // dV += P^T dO, dK += dS^T Q over four 16-row steps x four 32-column blocks
-        {
-            bf16x8 pf[4], df[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int b = u >> 1, x = (u & 1) * 8;
-                pf[u] = pack_bf16x8(s[b][x], s[b][x + 1], s[b][x + 2], s[b][x + 3], s[b][x + 4], s[b][x + 5], s[b][x + 6], s[b][x + 7]);
-                df[u] = pack_bf16x8(dp[b][x], dp[b][x + 1], dp[b][x + 2], dp[b][x + 3], dp[b][x + 4], dp[b][x + 5], dp[b][x + 6], dp[b][x + 7]);
-            }
-            const int jj = j16 >> 2, cl = 2 * grp2 + ((j16 & 3) >> 1);
-            auto tr_off = [&](int st, int second) {
-                const int u = st >> 2, db = st & 3;
-                const int r = 16 * u + 4 * hh + jj + 8 * second;
-                const int pos = (((db ^ jj) << 2) | (cl ^ (hh + 2 * second)));
-                return r * D + (pos << 3) + 4 * (j16 & 1);
-            };
-            constexpr int PF = 3;
-            bf16x8 gr[PF], qr[PF];
-#pragma unroll
-            for (int st = 0; st < PF; ++st) {
-                gr[st] = lds_tr_pair(&Gs[tr_off(st, 0)], &Gs[tr_off(st, 1)]);
-                qr[st] = lds_tr_pair(&Qs[tr_off(st, 0)], &Qs[tr_off(st, 1)]);
-            }
-#pragma unroll
-            for (int st = 0; st < 16; ++st) {
-                const bf16x8 gf = gr[st % PF], qf = qr[st % PF];
-                if (st + PF < 16) {
-                    gr[st % PF] = lds_tr_pair(&Gs[tr_off(st + PF, 0)], &Gs[tr_off(st + PF, 1)]);
-                    qr[st % PF] = lds_tr_pair(&Qs[tr_off(st + PF, 0)], &Qs[tr_off(st + PF, 1)]);
-                }
-                dv_acc[st & 3] = mfma32(pf[st >> 2], gf, dv_acc[st & 3]);
-                dk_acc[st & 3] = mfma32(df[st >> 2], qf, dk_acc[st & 3]);
-            }
+        for (int st = 0; st < 8; ++st) {
+            const bf16x8 gf = ra[(24 + st) % PF], qf = rb_[(24 + st) % PF];
+            if (st + PF < 8) load_tr(1, st + PF, (24 + st) % PF);
+            dv_acc[st & 3] = mfma32(pf[2 + (st >> 2)], gf, dv_acc[st & 3]);
+            dk_acc[st & 3] = mfma32(df[2 + (st >> 2)], qf, dk_acc[st & 3]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // Tile order: first the tiles that need masking (the leading, partly visible q tiles and a ragged last
+    // tile), then the fully visible ones -- two plain loops, one instantiation of the body each.
+    const int n_all = n_qtiles - qt_begin;
+    if (n_all > 0) {
+        const bool ragged = n_qtiles * TM > g.lq;
+        const int lead = (qt_full < n_qtiles ? qt_full : n_qtiles) - qt_begin;     // partly visible tiles
+        const bool extra = ragged && qt_begin + lead < n_qtiles;                    // ragged last tile not among them
+        const int n_masked = lead + (extra ? 1 : 0);
+        auto tile_of = [&](int i) { return i < lead ? qt_begin + i : (i < n_masked ? n_qtiles - 1 : qt_begin + lead + (i - n_masked)); };
+        fetch_tile(tile_of(0), 0);
+        int i = 0;
+        for (; i < n_masked; ++i) {
+            // publish tile i: wait for this wavefront's outstanding global->LDS loads, then barrier
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (i + 1 < n_all) fetch_tile(tile_of(i + 1), (i + 1) & 1);
+            tile_body(i & 1, std::true_type{});
+        }
+        for (; i < n_all; ++i) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (i + 1 < n_all) fetch_tile(tile_of(i + 1), (i + 1) & 1);
+            tile_body(i & 1, std::false_type{});
         }
     }
     // dK / dV: lane holds column d = 32*db + l32; register r holds key 32*wave + 8*(r/4) + 4*hh + r%4

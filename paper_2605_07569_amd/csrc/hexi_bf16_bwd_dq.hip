@@ -182,18 +182,22 @@ __global__ void __launch_bounds__(256, 2) bwd_dq_bf16_kernel(const BwdArgs a, co
 #pragma unroll
         for (int st = 0; st < PFK; ++st) ktr[st] = lds_tr_pair(&Ks[kt_off(st, 0)], &Ks[kt_off(st, 1)]);
 
-        // P^T and dS^T in place (s <- P, dp <- dS); keys the row cannot see get P = 0
+        // P^T into s; keys the row cannot see get P = 0 (one uniform branch per tile); then dS^T into dp
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float p = fast_exp2(fmaf(s[b][r], c_log2, neg_lse2));
-                if (partial) {
-                    const int kvl = 32 * b + 8 * (r >> 2) + 4 * hh + (r & 3);
-                    if (sm.kpos[buf][kvl] > my_pos) p = 0.f;
-                }
-                dp[b][r] = p * (dp[b][r] - delta);
-            }
+            for (int r = 0; r < 16; ++r) s[b][r] = fast_exp2(fmaf(s[b][r], c_log2, neg_lse2));
+        if (partial) {
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if (sm.kpos[buf][32 * b + 8 * (r >> 2) + 4 * hh + (r & 3)] > my_pos) s[b][r] = 0.f;
+        }
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) dp[b][r] = s[b][r] * (dp[b][r] - delta);
         bf16x8 dsf[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
