@@ -161,8 +161,19 @@ __global__ void __launch_bounds__(256) bwd_dkdv_bf16_kernel(const BwdArgs a, con
     // Each step (2 MFMAs, their LDS prefetches, 2 elements of VALU work) ends in a scheduling barrier,
     // so the hand-written interleave is what gets issued.  MASKED is a compile-time flag: masked tiles
     // take a copy of the body with selects, unmasked ones carry no per-element masking at all.
-    auto tile_body = [&](int buf, auto masked_c) __attribute__((always_inline)) {
+    // Lane parts of the LDS addresses (elements): everything else (q block, step, buffer) is a compile-time
+    // offset, so the reads need no address arithmetic inside the loop.
+    int nat_lane[8], tr_lane[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) nat_lane[ks] = l32 * D + (((2 * ks + hh) ^ sw_l32) << 3);
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {   // x = 2*db + second
+        const int db = x >> 1, second = x & 1;
+        tr_lane[x] = (4 * hh + jj + 8 * second) * D + ((((db ^ jj) << 2) | (cl ^ (hh + 2 * second))) << 3) + 4 * (j16 & 1);
+    }
+    auto tile_body = [&](auto buf_c, auto masked_c) __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked_c)::value;
+        constexpr int buf = decltype(buf_c)::value;
         const uint16_t* Qs = &sm.q[buf][0];
         const uint16_t* Gs = &sm.g[buf][0];
         f32x16 s[2], dp[2];
@@ -171,13 +182,8 @@ __global__ void __launch_bounds__(256) bwd_dkdv_bf16_kernel(const BwdArgs a, con
         constexpr int PF = 3;             // LDS fragments requested this many steps ahead of their MFMA
         bf16x8 ra[PF], rb_[PF];
 
-        auto nat_off = [&](int b, int ks) { return (32 * b + l32) * D + (((2 * ks + hh) ^ sw_l32) << 3); };
-        auto tr_off = [&](int b, int st, int second) {
-            const int u = 2 * b + (st >> 2), db = st & 3;
-            const int r = 16 * u + 4 * hh + jj + 8 * second;
-            const int pos = (((db ^ jj) << 2) | (cl ^ (hh + 2 * second)));
-            return r * D + (pos << 3) + 4 * (j16 & 1);
-        };
+        auto nat_off = [&](int b, int ks) { return nat_lane[ks] + 32 * b * D; };
+        auto tr_off = [&](int b, int st, int second) { return tr_lane[2 * (st & 3) + second] + 16 * (2 * b + (st >> 2)) * D; };
         auto load_nat = [&](int b, int ks, int slot) {
             ra[slot] = *reinterpret_cast<const bf16x8*>(&Qs[nat_off(b, ks)]);
             rb_[slot] = *reinterpret_cast<const bf16x8*>(&Gs[nat_off(b, ks)]);
@@ -273,20 +279,29 @@ __global__ void __launch_bounds__(256) bwd_dkdv_bf16_kernel(const BwdArgs a, con
         const int n_masked = lead + (extra ? 1 : 0);
         auto tile_of = [&](int i) { return i < lead ? qt_begin + i : (i < n_masked ? n_qtiles - 1 : qt_begin + lead + (i - n_masked)); };
         fetch_tile(tile_of(0), 0);
+        // one tile: publish it (wait for this wavefront's outstanding global->LDS loads, then barrier),
+        // start fetching the next one into the other buffer, compute
+        auto step = [&](int i, auto buf_c, auto masked_c) __attribute__((always_inline)) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (i + 1 < n_all) fetch_tile(tile_of(i + 1), decltype(buf_c)::value ^ 1);
+            tile_body(buf_c, masked_c);
+        };
+        using B0 = std::integral_constant<int, 0>;
+        using B1 = std::integral_constant<int, 1>;
         int i = 0;
-        for (; i < n_masked; ++i) {
-            // publish tile i: wait for this wavefront's outstanding global->LDS loads, then barrier
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-            if (i + 1 < n_all) fetch_tile(tile_of(i + 1), (i + 1) & 1);
-            tile_body(i & 1, std::true_type{});
+        // masked tiles (buffer parity follows i), then unmasked tiles two at a time
+        for (; i + 1 < n_masked; i += 2) {
+            step(i, B0{}, std::true_type{});
+            step(i + 1, B1{}, std::true_type{});
         }
-        for (; i < n_all; ++i) {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-            if (i + 1 < n_all) fetch_tile(tile_of(i + 1), (i + 1) & 1);
-            tile_body(i & 1, std::false_type{});
+        if (i < n_masked) { step(i, B0{}, std::true_type{}); ++i; }
+        if (i < n_all && (i & 1)) { step(i, B1{}, std::false_type{}); ++i; }
+        for (; i + 1 < n_all; i += 2) {
+            step(i, B0{}, std::false_type{});
+            step(i + 1, B1{}, std::false_type{});
         }
+        if (i < n_all) step(i, B0{}, std::false_type{});
     }
     // dK / dV: lane holds column d = 32*db + l32; register r holds key 32*wave + 8*(r/4) + 4*hh + r%4
 #pragma unroll
