@@ -12,6 +12,7 @@
 // each (row, head) belongs to exactly one workgroup of the launch).
 #include "hexi_internal.h"
 #include "hexi_mfma.h"
+#include <type_traits>
 
 namespace {
 
@@ -128,95 +129,124 @@ __global__ void __launch_bounds__(256, 2) bwd_dq_bf16_kernel(const BwdArgs a, co
     const int sw_l32 = swz_row(l32);
     const int jj = j16 >> 2, cl = 2 * grp2 + ((j16 & 3) >> 1);
 
-    fetch_tile(0, 0);
-    for (int tile = 0; tile < n_tiles; ++tile) {
-        const int buf = tile & 1;
-        const bool partial = tile >= n_full_tiles;
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (tile + 1 < n_tiles) fetch_tile(tile + 1, buf ^ 1);
+    // Lane parts of the LDS addresses (elements); block, step and buffer are compile-time offsets.
+    int nat_lane[8], tr_lane[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) nat_lane[ks] = l32 * D + (((2 * ks + hh) ^ sw_l32) << 3);
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {   // x = 2*db + second
+        const int db = x >> 1, second = x & 1;
+        tr_lane[x] = (4 * hh + jj + 8 * second) * D + ((((db ^ jj) << 2) | (cl ^ (hh + 2 * second))) << 3) + 4 * (j16 & 1);
+    }
 
+    // One 64-key tile.  The two 32-key blocks are staggered so that the VALU work of one block sits between
+    // MFMAs of the other in program order:
+    //   A: S^T/dP^T(block 0) | B: S^T/dP^T(block 1) + VALU(block 0) | C: dQ^T(block 0) + VALU(block 1) | D: dQ^T(block 1)
+    // Every step ends in a scheduling barrier so that this interleave is what gets issued.
+    auto tile_body = [&](auto buf_c, auto masked_c) __attribute__((always_inline)) {
+        constexpr bool MASKED = decltype(masked_c)::value;
+        constexpr int buf = decltype(buf_c)::value;
         const uint16_t* Ks = &sm.k[buf][0];
         const uint16_t* Vs = &sm.v[buf][0];
-        // S^T[key][q] and dP^T[key][q] for two 32-key blocks
         f32x16 s[2], dp[2];
+        bf16x8 dsf[4];
+        constexpr int PF = 2;
+        bf16x8 ra[PF], rb_[PF];
+        auto load_nat = [&](int b, int ks, int slot) {
+            ra[slot] = *reinterpret_cast<const bf16x8*>(&Ks[nat_lane[ks] + 32 * b * D]);
+            rb_[slot] = *reinterpret_cast<const bf16x8*>(&Vs[nat_lane[ks] + 32 * b * D]);
+        };
+        // K^T fragment of 16-key step u (= 2*b + st/4... see callers) and 32-column block db
+        auto load_tr = [&](int u, int db, int slot) {
+            ra[slot] = lds_tr_pair(&Ks[tr_lane[2 * db] + 16 * u * D], &Ks[tr_lane[2 * db + 1] + 16 * u * D]);
+        };
+        auto valu2 = [&](int b, int e) {
+#pragma unroll
+            for (int x = e; x < e + 2; ++x) {
+                float p = fast_exp2(fmaf(s[b][x], c_log2, neg_lse2));
+                if (MASKED) p = (sm.kpos[buf][32 * b + 8 * (x >> 2) + 4 * hh + (x & 3)] > my_pos) ? 0.f : p;
+                dp[b][x] = p * (dp[b][x] - delta);
+            }
+        };
+        auto pack = [&](int b, int half) {
+            const int x = 8 * half;
+            dsf[2 * b + half] = pack_bf16x8(dp[b][x], dp[b][x + 1], dp[b][x + 2], dp[b][x + 3], dp[b][x + 4], dp[b][x + 5], dp[b][x + 6], dp[b][x + 7]);
+        };
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) { s[b][r] = 0.f; dp[b][r] = 0.f; }
-        {
-            auto frag_off = [&](int st) { return (32 * (st & 1) + l32) * D + (((2 * (st >> 1) + hh) ^ sw_l32) << 3); };
-            constexpr int PF = 3;
-            bf16x8 kr[PF], vr[PF];
+        // phase A (global steps 0..7)
 #pragma unroll
-            for (int st = 0; st < PF; ++st) {
-                kr[st] = *reinterpret_cast<const bf16x8*>(&Ks[frag_off(st)]);
-                vr[st] = *reinterpret_cast<const bf16x8*>(&Vs[frag_off(st)]);
-            }
+        for (int ks = 0; ks < PF; ++ks) load_nat(0, ks, ks);
 #pragma unroll
-            for (int st = 0; st < 16; ++st) {
-                const bf16x8 kf = kr[st % PF], vf = vr[st % PF];
-                if (st + PF < 16) {
-                    kr[st % PF] = *reinterpret_cast<const bf16x8*>(&Ks[frag_off(st + PF)]);
-                    vr[st % PF] = *reinterpret_cast<const bf16x8*>(&Vs[frag_off(st + PF)]);
-                }
-                s[st & 1] = mfma32(kf, qf[st >> 1], s[st & 1]);
-                dp[st & 1] = mfma32(vf, gf[st >> 1], dp[st & 1]);
-            }
-            HEXI_SCHED_DSREAD(2 * PF);
-#pragma unroll
-            for (int st = 0; st < 16; ++st) {
-                HEXI_SCHED_MFMA(2);
-                if (st + PF < 16) HEXI_SCHED_DSREAD(2);
-            }
+        for (int ks = 0; ks < 8; ++ks) {
+            const bf16x8 kf = ra[ks % PF], vf = rb_[ks % PF];
+            if (ks + PF < 8) load_nat(0, ks + PF, ks % PF);
+            else load_nat(1, ks + PF - 8, ks % PF);
+            s[0] = mfma32(kf, qf[ks], s[0]);
+            dp[0] = mfma32(vf, gf[ks], dp[0]);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        // first K^T fragments on their way while the VALU part runs
-        auto kt_off = [&](int st, int second) {
-            const int u = st >> 2, db = st & 3;
-            const int r = 16 * u + 4 * hh + jj + 8 * second;
-            const int pos = (((db ^ jj) << 2) | (cl ^ (hh + 2 * second)));
-            return r * D + (pos << 3) + 4 * (j16 & 1);
-        };
-        constexpr int PFK = 4;
-        bf16x8 ktr[PFK];
+        // phase B (global steps 8..15): block 1 products, block 0 VALU
 #pragma unroll
-        for (int st = 0; st < PFK; ++st) ktr[st] = lds_tr_pair(&Ks[kt_off(st, 0)], &Ks[kt_off(st, 1)]);
-
-        // P^T into s; keys the row cannot see get P = 0 (one uniform branch per tile); then dS^T into dp
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[b][r] = fast_exp2(fmaf(s[b][r], c_log2, neg_lse2));
-        if (partial) {
-#pragma unroll
-            for (int b = 0; b < 2; ++b)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (sm.kpos[buf][32 * b + 8 * (r >> 2) + 4 * hh + (r & 3)] > my_pos) s[b][r] = 0.f;
+        for (int ks = 0; ks < 8; ++ks) {
+            const bf16x8 kf = ra[(8 + ks) % PF], vf = rb_[(8 + ks) % PF];
+            if (ks + PF < 8) load_nat(1, ks + PF, (8 + ks) % PF);
+            else load_tr((ks + PF - 8) >> 2, (ks + PF - 8) & 3, (8 + ks) % PF);
+            s[1] = mfma32(kf, qf[ks], s[1]);
+            dp[1] = mfma32(vf, gf[ks], dp[1]);
+            valu2(0, 2 * ks);
+            if (ks == 4) pack(0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
+        pack(0, 1);
+        // phase C (global steps 16..23): dQ^T += K^T dS^T for 16-key steps 0,1 (block 0); block 1 VALU
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) dp[b][r] = s[b][r] * (dp[b][r] - delta);
-        bf16x8 dsf[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int b = u >> 1, x = (u & 1) * 8;
-            dsf[u] = pack_bf16x8(dp[b][x], dp[b][x + 1], dp[b][x + 2], dp[b][x + 3], dp[b][x + 4], dp[b][x + 5], dp[b][x + 6], dp[b][x + 7]);
-        }
-        // dQ^T[d][q] += K^T dS^T over four 16-key steps x four 32-column blocks
-#pragma unroll
-        for (int st = 0; st < 16; ++st) {
-            const bf16x8 kt = ktr[st % PFK];
-            if (st + PFK < 16) ktr[st % PFK] = lds_tr_pair(&Ks[kt_off(st + PFK, 0)], &Ks[kt_off(st + PFK, 1)]);
+        for (int st = 0; st < 8; ++st) {
+            const bf16x8 kt = ra[(16 + st) % PF];
+            if (st + PF < 8) load_tr((st + PF) >> 2, (st + PF) & 3, (16 + st) % PF);
+            else load_tr(2 + ((st + PF - 8) >> 2), (st + PF - 8) & 3, (16 + st) % PF);
             dq[st & 3] = mfma32(kt, dsf[st >> 2], dq[st & 3]);
+            valu2(1, 4 * (st >> 1) + 2 * (st & 1));
+            if (st == 4) pack(1, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
+        pack(1, 1);
+        // phase D (global steps 24..31): 16-key steps 2,3 (block 1)
 #pragma unroll
-        for (int st = 0; st < 16; ++st) {
-            HEXI_SCHED_MFMA(1);
-            if (st + PFK < 16) HEXI_SCHED_DSREAD(2);
+        for (int st = 0; st < 8; ++st) {
+            const bf16x8 kt = ra[(24 + st) % PF];
+            if (st + PF < 8) load_tr(2 + ((st + PF) >> 2), (st + PF) & 3, (24 + st) % PF);
+            dq[st & 3] = mfma32(kt, dsf[2 + (st >> 2)], dq[st & 3]);
+            __builtin_amdgcn_sched_barrier(0);
         }
+    };
+
+    fetch_tile(0, 0);
+    // one tile: publish it (wait for this wavefront's outstanding global->LDS loads, then barrier), start
+    // fetching the next one into the other buffer, compute
+    auto step = [&](int tile, auto buf_c, auto masked_c) __attribute__((always_inline)) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tile + 1 < n_tiles) fetch_tile(tile + 1, decltype(buf_c)::value ^ 1);
+        tile_body(buf_c, masked_c);
+    };
+    using B0 = std::integral_constant<int, 0>;
+    using B1 = std::integral_constant<int, 1>;
+    // unmasked tiles two at a time, then the masked tail (buffer = tile parity throughout)
+    int tile = 0;
+    for (; tile + 1 < n_full_tiles; tile += 2) {
+        step(tile, B0{}, std::false_type{});
+        step(tile + 1, B1{}, std::false_type{});
     }
+    if (tile < n_full_tiles) { step(tile, B0{}, std::false_type{}); ++tile; }
+    if (tile < n_tiles && (tile & 1)) { step(tile, B1{}, std::true_type{}); ++tile; }
+    for (; tile + 1 < n_tiles; tile += 2) {
+        step(tile, B0{}, std::true_type{});
+        step(tile + 1, B1{}, std::true_type{});
+    }
+    if (tile < n_tiles) step(tile, B0{}, std::true_type{});
 
     if (my_row >= g.lq) return;
     // lane (row l32, half hh): register 4*b + t of block db holds d = 32*db + 8*b + 4*hh + t
