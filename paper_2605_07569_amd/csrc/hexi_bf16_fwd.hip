@@ -1,51 +1,109 @@
-// bf16 forward ring step for gfx950: one workgroup (4 wavefronts) per (128-row q tile, q head),
-// two workgroups per CU.
+// bf16 forward ring step for gfx950: one workgroup of 8 wavefronts per (256-row q tile, q head), one
+// workgroup per CU.
 //
-// The scores are computed transposed, S^T = K Q^T, so that every lane owns one query row: the
-// softmax state (running max, running sums) is a per-lane scalar, the row reductions are in-lane
-// plus one exchange between the two half-waves, and the accumulator registers holding P^T are
-// already in MFMA operand order for O^T += V^T P^T.  Q stays in registers for the whole chunk.
+// Ping-pong schedule.  On this hardware a wavefront that has just issued an MFMA cannot issue its own
+// VALU work for most of the MFMA's duration, but ANOTHER wavefront of the same SIMD can: a wavefront
+// issuing only MFMAs runs the matrix pipe at its full rate while its SIMD partner issues VALU
+// instructions at nearly their solo rate.  The workgroup is therefore two groups of four wavefronts
+// (wavefront w and w + 4 share a SIMD), each group owning 128 query rows, that alternate between
+//   M(t): the matrix phase  -- O^T += V^T P^T of tile t-1, then S^T = K Q^T of tile t (32 MFMAs), and
+//   V(t): the vector phase  -- softmax numerators of tile t, P rounded to bf16 operand slots,
+// one workgroup barrier per phase, group 1 running one phase behind group 0, so that every SIMD always
+// has one wavefront in a matrix phase and one in a vector phase.  The vector-phase group also issues the
+// direct global->LDS loads of upcoming tiles (group 1 fetches K four tiles ahead, group 0 fetches V two
+// tiles ahead; four LDS buffers per tensor).
 //
-// K / V tiles (64 keys) are double-buffered in LDS and fetched one tile ahead with direct
-// global->LDS loads; one barrier per tile.  The tiles are XOR-swizzled (no padding) so that both the
-// 128-bit row reads of K and the transposed 64-bit reads of V are bank-conflict free.  KV tiles that
-// lie wholly in the visible past of the q tile skip all masking; tiles wholly in the future are
-// never visited.
+// As before the scores are computed transposed (S^T = K Q^T) so that every lane owns one query row,
+// softmax state is a per-lane scalar, and the accumulator registers holding P^T are already in MFMA
+// operand order for O^T += V^T P^T.  K / V tiles (64 keys) are XOR-swizzled in LDS so that the 128-bit
+// row reads of K and the transposed 64-bit reads of V are bank-conflict free.
 //
-// Softmax runs in base 2 with the scale folded into one FMA per score.  The running maximum is only
-// raised when a tile exceeds it by more than 2^8 (then O and the sums are rescaled); otherwise the
-// probabilities are formed against the stale maximum, which keeps them below 2^8 and leaves the
-// result unchanged because the same reference enters the sums.
+// Softmax reference.  The vector phase must stay short (it is the co-limiter), so the fast path does not
+// track a running maximum: the reference m of a row is fixed after its first tile (the row maximum over
+// that tile's visible keys) and every later probability is exp2(s - m) against that same m.  This is
+// exact as long as nothing over- or underflows, which fp32 / bf16 exponents guarantee unless a later
+// score differs from the first tile's maximum by more than about 2^100.  Each row checks its final sum
+// against [2^-60, 2^60]; if any row of the workgroup fails, the whole workgroup repeats its tiles with
+// the exact online-softmax path (running maximum, lazy rescale).  Rows in the fast path keep two sums:
+// the exact one defines the LSE, the one of the bf16-rounded probabilities normalises O.
 #include "hexi_internal.h"
 #include "hexi_mfma.h"
+#include <type_traits>
+#include <utility>
 
 namespace {
 
 constexpr int D = 128;
-constexpr int TM = 128;          // q rows per workgroup (32 per wavefront)
-constexpr int TN = 64;           // keys per tile
+constexpr int TN = 64;             // keys per tile
+constexpr int NB = 4;              // LDS buffers per tensor
+constexpr int GROUP_ROWS = 128;    // q rows per wavefront group (32 per wavefront)
+constexpr int WG_ROWS = 256;       // q rows per workgroup
+// LDS rows are padded instead of swizzled, so that every operand fragment sits at (one per-lane base
+// register) + (compile-time offset): K rows take 272 bytes (16 consecutive rows then spread over all 64
+// banks for the 128-bit row reads), V rows 320 bytes (the 4 rows x 64 bytes of a transposed 64-bit read
+// then spread over all 64 banks).
+constexpr int K_ROW_BYTES = 272, V_ROW_BYTES = 320;
+constexpr int K_TILE_BYTES = TN * K_ROW_BYTES;   // 17 KB = 17 wave-wide 1 KB transfers
+constexpr int V_TILE_BYTES = TN * V_ROW_BYTES;   // 20 KB = 20 transfers
+constexpr int DMA_PER_WAVE = 5;                  // transfers per wavefront per tile (K: 3 of the 20 slots are dummies)
+constexpr int O_STAGE_STRIDE = D + 4;   // floats per staged output row (epilogue)
+constexpr int K_AHEAD = 4;         // group 1 fetches K(t + 4) during V(t)
+constexpr int V_AHEAD = 2;         // group 0 fetches V(t + 2) during V(t)
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 constexpr float NEG_BIG = -1.0e30f;   // finite stand-in for "no key seen yet"
 constexpr float RESCALE_SLACK = 8.0f;
+constexpr float SUM_LO = 8.6736174e-19f;   // 2^-60
+constexpr float SUM_HI = 1.1529215e18f;    // 2^60
 
 __device__ __forceinline__ int swz_row(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
 
 struct FwdSmem {
-    uint16_t k[2][TN * D];   // 2 x 16 KB
-    uint16_t v[2][TN * D];   // 2 x 16 KB
-    int kpos[2][TN];
-#ifdef EXP_BIG_LDS
-    int pad[12000];
-#endif
+    unsigned char k[NB][K_TILE_BYTES];   // 4 x 17 KB
+    unsigned char v[NB][V_TILE_BYTES];   // 4 x 20 KB
+    int kpos[2 * NB][TN];     // key positions of the tiles that need a mask, written K_AHEAD tiles ahead
+    unsigned char dump[1024]; // destination of the dummy transfers
+    // the epilogue stages 8 x (32 x 132 + 32) floats over the start of this struct
 };
+static_assert(sizeof(FwdSmem) >= 8 * (32 * O_STAGE_STRIDE + 32) * 4, "epilogue staging does not fit");
 
-__global__ void __launch_bounds__(256, 2) fwd_bf16_kernel(const FwdArgs a, const int n_q_tiles)
+template <int N> using IC = std::integral_constant<int, N>;
+
+// f(IC<FIRST>{}), ..., f(IC<LAST - 1>{})
+template <int FIRST, int... I, class F> __device__ __forceinline__ void for_range_impl(std::integer_sequence<int, I...>, F& f)
+{
+    (f(IC<FIRST + I>{}), ...);
+}
+template <int FIRST, int LAST, class F> __device__ __forceinline__ void for_range(F& f)
+{
+    for_range_impl<FIRST>(std::make_integer_sequence<int, LAST - FIRST>{}, f);
+}
+
+__device__ __forceinline__ void wait_vm(int allowed_tiles)
+{
+    // each wavefront issues DMA_PER_WAVE global->LDS loads per tile; they complete in order
+    static_assert(DMA_PER_WAVE == 5, "wait counts below assume 5 transfers per tile");
+    if (allowed_tiles >= 3) asm volatile("s_waitcnt vmcnt(15)" ::: "memory");
+    else if (allowed_tiles == 2) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+    else if (allowed_tiles == 1) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+__device__ __forceinline__ void wg_barrier()
+{
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+__global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const int n_q_tiles)
 {
     const AttnGeom& g = a.g;
     __shared__ __attribute__((aligned(1024))) FwdSmem sm;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = wave >> 2, wg = wave & 3;
     const int l32 = lane & 31, hh = lane >> 5;
     const int grp2 = (lane >> 4) & 1, j16 = lane & 15;
 
@@ -63,8 +121,9 @@ __global__ void __launch_bounds__(256, 2) fwd_bf16_kernel(const FwdArgs a, const
     const int h = unit / n_q_tiles;
     const int q_tile = n_q_tiles - 1 - (unit - h * n_q_tiles);
     const int kvh = g.kv_of_q[h];
-    const int row0 = q_tile * TM;
-    const int my_row = row0 + 32 * wave + l32;
+    const int row0 = q_tile * WG_ROWS;
+    const int grow0 = row0 + GROUP_ROWS * grp;
+    const int my_row = grow0 + 32 * wg + l32;
     const int my_row_c = my_row < g.lq ? my_row : g.lq - 1;
     const int my_pos = my_row < g.lq ? seg_pos_of_row(g.qs, my_row) : -1;
 
@@ -72,13 +131,14 @@ __global__ void __launch_bounds__(256, 2) fwd_bf16_kernel(const FwdArgs a, const
     const uint16_t* k = static_cast<const uint16_t*>(a.k) + (long long)kvh * g.kv_stride_head;
     const uint16_t* v = static_cast<const uint16_t*>(a.v) + (long long)kvh * g.kv_stride_head;
 
-    // visible columns of this q tile form a prefix of the chunk; columns visible to every row of
-    // the tile form a (shorter) prefix
-    const int last_row = (row0 + TM < g.lq ? row0 + TM : g.lq) - 1;
-    const int n_vis = seg_rows_le(g.ks, seg_pos_of_row(g.qs, last_row));
-    const int n_all = seg_rows_le(g.ks, seg_pos_of_row(g.qs, row0));
-    const int n_tiles = (n_vis + TN - 1) / TN;
-    const int n_full_tiles = n_all / TN;
+    // Visible keys of a row range form a prefix of the chunk; keys visible to every row of the range a
+    // shorter prefix.  n_full_g: tiles this group needs no mask for (the rest are masked by position).
+    // NT: tiles the workgroup streams (those of its last rows); n_full_wg: tiles no row needs a mask for.
+    int n_full_g = 0;
+    if (grow0 < g.lq) n_full_g = seg_rows_le(g.ks, seg_pos_of_row(g.qs, grow0)) / TN;
+    const int wg_last_row = (row0 + WG_ROWS < g.lq ? row0 + WG_ROWS : g.lq) - 1;
+    const int NT = (seg_rows_le(g.ks, seg_pos_of_row(g.qs, wg_last_row)) + TN - 1) / TN;
+    const int n_full_wg = seg_rows_le(g.ks, seg_pos_of_row(g.qs, row0)) / TN;
 
     // Q^T operand fragments: lane (row l32, half hh) holds d = 16*ks + 8*hh .. +7
     bf16x8 qf[8];
@@ -90,220 +150,271 @@ __global__ void __launch_bounds__(256, 2) fwd_bf16_kernel(const FwdArgs a, const
         for (int ks = 0; ks < 8; ++ks) pin(qf[ks]);
     }
 
-    // Direct global->LDS fetch of one K/V tile: 16 wave-instructions of 1 KB per tensor, 4 per
-    // wavefront; lane L of instruction i fills chunk position L%16 of row 4*i + L/16 with the
-    // chunk (L%16) ^ swz_row(row).
-    int fetch_off[4];
+    // Direct global->LDS fetch of one tile by the four wavefronts of a group.  A transfer is one wave-wide
+    // instruction: lane L writes the 16 bytes at (transfer * 1024 + 16 * L) of the tile's LDS image and reads
+    // them from wherever the kernel points it, here the 16-byte piece of the key row that belongs there (pad
+    // pieces re-read piece 0).  Wavefront wg issues transfers wg, wg + 4, ..., wg + 16; transfer numbers past
+    // the tile's end go to a dump area.
+    const int row_bytes = grp ? K_ROW_BYTES : V_ROW_BYTES;
+    const int n_xfer = grp ? K_TILE_BYTES / 1024 : V_TILE_BYTES / 1024;
+    uint32_t fetch_off[DMA_PER_WAVE];   // byte offsets from the tile's first key
+    int fetch_row[DMA_PER_WAVE];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int r = (wave * 4 + i) * 4 + (lane >> 4);
-        fetch_off[i] = r * (int)g.kv_stride_tok + (((lane & 15) ^ swz_row(r)) << 3);
+    for (int i = 0; i < DMA_PER_WAVE; ++i) {
+        const int pos = (wg + 4 * i) * 1024 + 16 * lane;
+        int r = pos / row_bytes, c = (pos - r * row_bytes) >> 4;
+        if (wg + 4 * i >= n_xfer) r = 0;
+        if (c >= 16) c = 0;
+        fetch_row[i] = r;
+        fetch_off[i] = 2u * (uint32_t)(r * (int)g.kv_stride_tok + c * 8);
     }
     const uint32_t lds_k = (uint32_t)(uintptr_t)(&sm.k[0][0]), lds_v = (uint32_t)(uintptr_t)(&sm.v[0][0]);
-    auto fetch_tile = [&](int tile, int buf) {
+    const uint32_t lds_dump = (uint32_t)(uintptr_t)(&sm.dump[0]);
+    const uint16_t* fetch_src = grp ? k : v;                 // group 1 streams K, group 0 streams V
+    const uint32_t fetch_lds = grp ? lds_k : lds_v;
+    const int fetch_tile_bytes = grp ? K_TILE_BYTES : V_TILE_BYTES;
+    auto fetch_tile = [&](int tile) {
         const int col0 = tile * TN;
-        const uint32_t wk = __builtin_amdgcn_readfirstlane(lds_k + buf * (TN * D * 2) + wave * 4096);
-        const uint32_t wv = __builtin_amdgcn_readfirstlane(lds_v + buf * (TN * D * 2) + wave * 4096);
-        if (col0 + TN <= g.lc) {
-            const uint16_t* kb = k + (long long)col0 * g.kv_stride_tok;
-            const uint16_t* vb = v + (long long)col0 * g.kv_stride_tok;
+        const uint32_t dst = __builtin_amdgcn_readfirstlane(fetch_lds + (tile & (NB - 1)) * fetch_tile_bytes + wg * 1024);
+        const uint16_t* src = fetch_src + (long long)col0 * g.kv_stride_tok;
+        const bool ragged = col0 + TN > g.lc;   // last tile: clamp the key index (the extra keys are masked through their position)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                lds_dma16(kb + fetch_off[i], wk + i * 1024);
-                lds_dma16(vb + fetch_off[i], wv + i * 1024);
-            }
-        } else {   // ragged last tile: clamp the key index (the extra keys are masked through their position)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int r = (wave * 4 + i) * 4 + (lane >> 4);
-                const int c = (lane & 15) ^ swz_row(r);
-                const int col = col0 + r < g.lc ? col0 + r : g.lc - 1;
-                const long long off = (long long)col * g.kv_stride_tok + c * 8;
-                lds_dma16(k + off, wk + i * 1024);
-                lds_dma16(v + off, wv + i * 1024);
-            }
+        for (int i = 0; i < DMA_PER_WAVE; ++i) {
+            uint32_t off = fetch_off[i];
+            if (ragged && col0 + fetch_row[i] >= g.lc)
+                off -= 2u * (uint32_t)((col0 + fetch_row[i] - (g.lc - 1)) * (int)g.kv_stride_tok);
+            const uint32_t d = wg + 4 * i < n_xfer ? dst + i * 4096 : lds_dump;
+            lds_dma16_base(src, off, __builtin_amdgcn_readfirstlane(d));
         }
-        if (wave == 0 && tile >= n_full_tiles)
-            sm.kpos[buf][lane] = col0 + lane < g.lc ? seg_pos_of_row(g.ks, col0 + lane) : 0x7fffffff;
+        // global positions of the tile's keys, for the tiles some row needs a mask for
+        if (grp == 1 && wg == 0 && tile >= n_full_wg) {
+            sm.kpos[tile & (2 * NB - 1)][lane] = col0 + lane < g.lc ? seg_pos_of_row(g.ks, col0 + lane) : 0x7fffffff;
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
     };
 
+    // Lane parts of the LDS byte addresses; buffer, key block and step are compile-time offsets of the reads.
+    //   K fragment (ks, block b) of buffer B:   k_addr  + B * K_TILE_BYTES + 32 * b * K_ROW_BYTES + 32 * ks
+    //   V^T fragment (16-key step u, 32-column block db, half `second`) of buffer BV:
+    //        v_addr[BV / 2] + (BV % 2) * V_TILE_BYTES + (16 * u + 8 * second) * V_ROW_BYTES + 64 * db
+    // (two base registers for V: the offset field of an LDS read holds 16 bits).  A transposed read hands
+    // lane i of a 16-lane group the elements [row0 + e][col0 + i], e = 0..3, where lane j supplies the address
+    // of [row0 + j/4][col0 + 4*(j%4)].
+    const int jj = j16 >> 2;
+    const uint32_t k_addr = lds_k + l32 * K_ROW_BYTES + 16 * hh;
+    uint32_t v_addr[2];
+    v_addr[0] = lds_v + (4 * hh + jj) * V_ROW_BYTES + 2 * (16 * grp2 + 4 * (j16 & 3));
+    v_addr[1] = v_addr[0] + 2 * V_TILE_BYTES;
+
     f32x16 oacc[4];
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
-    float m_run = NEG_BIG, l_run = 0.f, lr_run = 0.f;
+    f32x16 s[2];
+    bf16x8 pf[4];
+    float m_run, l_run, lr_run, thr_raw;
     const float c_log2 = g.scale * LOG2E, inv_c_log2 = 1.0f / c_log2;
-    float thr_raw = NEG_BIG;   // any finite score exceeds it: the first visible tile always sets the maximum
-    const int sw_l32 = swz_row(l32);
-    const int jj = j16 >> 2, cl = 2 * grp2 + ((j16 & 3) >> 1);
 
-#ifdef EXP_TIMING
-    long long tacc[6] = {0, 0, 0, 0, 0, 0}; long long t0 = __builtin_amdgcn_s_memtime(), t1;
-#define TICK(i) { t1 = __builtin_amdgcn_s_memtime(); tacc[i] += t1 - t0; t0 = t1; }
-#else
-#define TICK(i)
-#endif
-    if (n_tiles > 0) fetch_tile(0, 0);
-    for (int tile = 0; tile < n_tiles; ++tile) {
-        const int buf = tile & 1;
-        const bool partial = tile >= n_full_tiles;
-        // publish tile: wait for this wavefront's outstanding global->LDS loads, then barrier
-        TICK(0)
-#ifndef EXP_NO_VMWAIT
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#endif
-        TICK(1)
-#ifndef EXP_NO_BARRIER
-        __syncthreads();
-#endif
-#ifdef EXP_NO_FETCH
-        if (tile + 1 < n_tiles && g.scale == 12345.f) fetch_tile(tile + 1, buf ^ 1);
-#else
-        if (tile + 1 < n_tiles) fetch_tile(tile + 1, buf ^ 1);
-#endif
-
-        TICK(2)
-        const uint16_t* Ks = &sm.k[buf][0];
-        const uint16_t* Vs = &sm.v[buf][0];
-        // S^T[key][q] for two 32-key blocks, LDS reads running ahead of the MFMAs
-        f32x16 s[2];
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[b][r] = 0.f;
-        {
-            auto frag_off = [&](int st) { return (32 * (st & 1) + l32) * D + (((2 * (st >> 1) + hh) ^ sw_l32) << 3); };
-            constexpr int PF = 4;
-            bf16x8 kr[PF];
-#pragma unroll
-            for (int st = 0; st < PF; ++st) kr[st] = *reinterpret_cast<const bf16x8*>(&Ks[frag_off(st)]);
-#pragma unroll
-            for (int st = 0; st < 16; ++st) {
-                const bf16x8 kf = kr[st % PF];
-                if (st + PF < 16) kr[st % PF] = *reinterpret_cast<const bf16x8*>(&Ks[frag_off(st + PF)]);
-                s[st & 1] = mfma32(kf, qf[st >> 1], s[st & 1]);
+    // Matrix phase on buffers (B + NB - 1) % NB (V of tile t-1) and B (K of tile t).  Steps 0..15:
+    // O^T[d][q] += V^T P^T, four 16-key steps x four 32-column blocks; steps 16..31: S^T[key][q] for two
+    // 32-key blocks.  [FIRST, LAST) selects the steps; operand fragments are requested PF steps ahead.
+    auto m_phase = [&](auto bc, auto first_c, auto last_c) __attribute__((always_inline)) {
+        constexpr int B = decltype(bc)::value, FIRST = decltype(first_c)::value, LAST = decltype(last_c)::value;
+        constexpr int PF = 4;
+        constexpr int BV = (B + NB - 1) % NB;
+        constexpr int KOFF = B * K_TILE_BYTES, VOFF = (BV % 2) * V_TILE_BYTES;
+        constexpr int NS = PF + 1;   // a fragment's registers are busy from its request until its MFMA
+        s16x4 ta[NS], tb[NS];
+        bf16x8 kb[NS];
+        auto issue = [&](auto stc) __attribute__((always_inline)) {
+            constexpr int st = decltype(stc)::value, slot = (st - FIRST) % NS;
+            if constexpr (st < 16) {
+                constexpr int u = st >> 2, db = st & 3;
+                lds_issue_tr16<VOFF + 16 * u * V_ROW_BYTES + 64 * db>(ta[slot], v_addr[BV / 2]);
+                lds_issue_tr16<VOFF + (16 * u + 8) * V_ROW_BYTES + 64 * db>(tb[slot], v_addr[BV / 2]);
+            } else {
+                constexpr int b = (st - 16) & 1, ks = (st - 16) >> 1;
+                lds_issue_b128<KOFF + 32 * b * K_ROW_BYTES + 32 * ks>(kb[slot], k_addr);
             }
-            // K fragments run 4 reads ahead of the MFMA that consumes them
-            HEXI_SCHED_DSREAD(PF);
-#pragma unroll
-            for (int st = 0; st < 16; ++st) {
-                HEXI_SCHED_MFMA(1);
-                if (st + PF < 16) HEXI_SCHED_DSREAD(1);
-            }
-        }
-#ifdef EXP_TIMING
-        asm volatile("s_nop 0" :: "v"(s[0][0]), "v"(s[1][15]));
-#endif
-        TICK(3)
-        // first V^T fragments can be on their way while the softmax runs
-        auto v_off = [&](int st, int second) {
-            const int u = st >> 2, db = st & 3;
-            const int r = 16 * u + 4 * hh + jj + 8 * second;
-            const int pos = (((db ^ jj) << 2) | (cl ^ (hh + 2 * second)));
-            return r * D + (pos << 3) + 4 * (j16 & 1);
         };
-        constexpr int PFV = 4;
-        bf16x8 vr[PFV];
-#pragma unroll
-        for (int st = 0; st < PFV; ++st) vr[st] = lds_tr_pair(&Vs[v_off(st, 0)], &Vs[v_off(st, 1)]);
+        auto step = [&](auto stc) __attribute__((always_inline)) {
+            constexpr int st = decltype(stc)::value, slot = (st - FIRST) % NS;
+            if constexpr (st + PF < LAST) issue(IC<st + PF>{});
+            // LDS reads younger than this step's fragment: those of the next PF steps that exist
+            constexpr int hi = st + PF < LAST ? st + PF : LAST - 1;
+            constexpr int n_tr = (hi < 16 ? hi : 15) - (st < 16 ? st : 15);      // steps in (st, hi] below 16
+            constexpr int younger = 2 * n_tr + ((hi - st) - n_tr);
+            if constexpr (st < 16) {
+                lds_wait<younger>(ta[slot], tb[slot]);
+                oacc[st & 3] = mfma32(join_halves(ta[slot], tb[slot]), pf[st >> 2], oacc[st & 3]);
+            } else {
+                constexpr int b = (st - 16) & 1, ks = (st - 16) >> 1;
+                lds_wait<younger>(kb[slot]);
+                const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                s[b] = mfma32(kb[slot], qf[ks], ks == 0 ? zero : s[b]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        __builtin_amdgcn_sched_barrier(0);
+        for_range<FIRST, (FIRST + PF < LAST ? FIRST + PF : LAST)>(issue);
+        for_range<FIRST, LAST>(step);
+    };
 
-#ifdef EXP_NO_SMAX
-        bf16x8 pf[4];
-        for (int u = 0; u < 4; ++u) { f32x4 t = {s[u >> 1][(u & 1) * 8], s[u >> 1][(u & 1) * 8 + 1], s[u >> 1][(u & 1) * 8 + 2], s[u >> 1][(u & 1) * 8 + 3]}; pf[u] = __builtin_bit_cast(bf16x8, t); }
-#else
-        if (partial) {
+    // Vector phase: probabilities of the tile whose scores sit in s[], rounded to bf16 operand slots.
+    // Two running sums: `l_run` of the exact values (it defines the LSE that the merge and the backward
+    // pass use) and `lr_run` of the rounded values (it normalises O, so that O is an exact convex
+    // combination with the weights the PV product really used).  Both are per-half partial sums; the two
+    // half-waves are added at the end.
+    //   MASKED: the tile needs the causal mask (key positions from LDS).
+    //   exact:  online softmax -- running maximum raised lazily (only when a tile exceeds it by more than
+    //           2^8; then O and the sums are rescaled).  Otherwise the reference is fixed by the first tile.
+    auto v_phase = [&](int buf, auto first_c, auto masked_c, const bool exact) __attribute__((always_inline)) {
+        constexpr bool MASKED = decltype(masked_c)::value, first_tile = decltype(first_c)::value;
+        if (MASKED) {
+            const int* kp = &sm.kpos[buf][0];
 #pragma unroll
             for (int b = 0; b < 2; ++b)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int kvl = 32 * b + 8 * (r >> 2) + 4 * hh + (r & 3);
-                    if (sm.kpos[buf][kvl] > my_pos) s[b][r] = -INFINITY;
+                for (int rb = 0; rb < 4; ++rb) {
+                    const int4 p4 = *reinterpret_cast<const int4*>(&kp[32 * b + 8 * rb + 4 * hh]);
+                    if (p4.x > my_pos) s[b][4 * rb] = -INFINITY;
+                    if (p4.y > my_pos) s[b][4 * rb + 1] = -INFINITY;
+                    if (p4.z > my_pos) s[b][4 * rb + 2] = -INFINITY;
+                    if (p4.w > my_pos) s[b][4 * rb + 3] = -INFINITY;
                 }
         }
-        float mx = max3(s[0][0], s[0][1], s[0][2]);
+        if (exact || first_tile) {
+            float mx = max3(s[0][0], s[0][1], s[0][2]);
 #pragma unroll
-        for (int r = 3; r < 15; r += 2) mx = max3(mx, s[0][r], s[0][r + 1]);
-        mx = max3(mx, s[0][15], s[1][0]);
+            for (int r = 3; r < 15; r += 2) mx = max3(mx, s[0][r], s[0][r + 1]);
+            mx = max3(mx, s[0][15], s[1][0]);
 #pragma unroll
-        for (int r = 1; r < 15; r += 2) mx = max3(mx, s[1][r], s[1][r + 1]);
-        mx = max_across_halves(max2(mx, s[1][15]));
-        // raise the running maximum only when this tile exceeds it by more than the slack
-        // (mx is the raw score; thr_raw = (m_run + slack) / c)
-        if (__any(mx > thr_raw)) {
-            const float m_new = fmaxf(m_run, mx * c_log2);
-            const float alpha = fast_exp2(m_run - m_new);
-            l_run *= alpha;
-            lr_run *= alpha;
+            for (int r = 1; r < 15; r += 2) mx = max3(mx, s[1][r], s[1][r + 1]);
+            mx = max_across_halves(max2(mx, s[1][15]));
+            if (exact) {
+                // mx is the raw score; thr_raw = (m_run + slack) / c
+                if (__any(mx > thr_raw)) {
+                    const float m_new = fmaxf(m_run, mx * c_log2);
+                    const float alpha = fast_exp2(m_run - m_new);
+                    l_run *= alpha;
+                    lr_run *= alpha;
+                    // (one multiply per register through inline assembly: written as vector arithmetic the
+                    // compiler splats alpha into 16 extra registers, which costs the hot loop a spill)
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+                    for (int db = 0; db < 4; ++db)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
-            m_run = m_new;
-            thr_raw = (m_run + RESCALE_SLACK) * inv_c_log2;
+                        for (int r = 0; r < 16; ++r) asm("v_mul_f32 %0, %1, %0" : "+v"(oacc[db][r]) : "v"(alpha));
+                    m_run = m_new;
+                    thr_raw = (m_run + RESCALE_SLACK) * inv_c_log2;
+                }
+            } else {
+                m_run = mx == -INFINITY ? 0.f : mx * c_log2;   // a row that sees nothing in the first tile sees nothing at all
+            }
         }
-        // probabilities, rounded to bf16 operand slots.  Two running sums: `l_run` of the exact
-        // values (it defines the LSE that the merge and the backward pass use) and `lr_run` of the
-        // rounded values (it normalises O, so that O is an exact convex combination with the
-        // weights the PV product really used and the rounding of a dominant key cancels).
-        float ps = 0.f, psr = 0.f;
-        bf16x8 pf[4];
+        // four independent partial sums per kind: a chain of 32 dependent additions would serialise the phase
+        float ps[4] = {0.f, 0.f, 0.f, 0.f}, psr[4] = {0.f, 0.f, 0.f, 0.f};
         const float neg_m = -m_run;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int b = u >> 1, x = (u & 1) * 8;
             float p[8];
 #pragma unroll
-#ifdef EXP_NO_EXP
-            for (int e = 0; e < 8; ++e) { p[e] = fmaf(s[b][x + e], c_log2, neg_m); ps += p[e]; }
-#else
-            for (int e = 0; e < 8; ++e) { p[e] = fast_exp2(fmaf(s[b][x + e], c_log2, neg_m)); ps += p[e]; }
-#endif
-            pf[u] = pack_bf16x8_sum(p[0], p[1], p[2], p[3], p[4], p[5], p[6], p[7], psr);
+            for (int e = 0; e < 8; ++e) { p[e] = fast_exp2(fmaf(s[b][x + e], c_log2, neg_m)); ps[e & 3] += p[e]; }
+            pf[u] = pack_bf16x8_sum4(p[0], p[1], p[2], p[3], p[4], p[5], p[6], p[7], psr);
         }
-        l_run += ps;       // per-half partial sums; the two halves are added at the end
-        lr_run += psr;
+        l_run += (ps[0] + ps[1]) + (ps[2] + ps[3]);
+        lr_run += (psr[0] + psr[1]) + (psr[2] + psr[3]);
+        // keep the whole vector phase on this side of the next barrier (nothing of it may drift into the
+        // matrix phase, where it would hold registers and steal issue slots from the MFMA stream)
+        asm volatile("" : "+v"(l_run), "+v"(lr_run), "+v"(pf[0]), "+v"(pf[1]), "+v"(pf[2]), "+v"(pf[3]));
+    };
 
-#endif
-#ifdef EXP_TIMING
-        asm volatile("s_nop 0" :: "v"(pf[3]));
-#endif
-        TICK(4)
-        // O^T[d][q] += V^T P^T over four 16-key steps x four 32-column blocks
+    // One pass over the workgroup's tiles.  Phase sequence of a group: M(0) V(0) M(1) V(1) ... M(NT), a
+    // barrier before every phase; group 1 starts one barrier late and group 0 ends with one extra.  Both
+    // groups walk all NT tiles (a group whose rows see fewer tiles masks the rest away), so the control
+    // flow is the same everywhere.
+    auto run = [&](const bool exact) __attribute__((always_inline)) {
 #pragma unroll
-        for (int st = 0; st < 16; ++st) {
-            const bf16x8 vf = vr[st % PFV];
-            if (st + PFV < 16) vr[st % PFV] = lds_tr_pair(&Vs[v_off(st + PFV, 0)], &Vs[v_off(st + PFV, 1)]);
-#ifndef EXP_NO_PV
-            oacc[st & 3] = mfma32(vf, pf[st >> 2], oacc[st & 3]);
-#else
-            if (st == 0) oacc[0] = mfma32(vf, pf[0], oacc[0]); if (st == 1) oacc[1] = mfma32(vf, pf[1], oacc[1]); if (st == 2) oacc[2] = mfma32(vf, pf[2], oacc[2]); if (st == 3) oacc[3] = mfma32(vf, pf[3], oacc[3]);
-#endif
-        }
+        for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int st = 0; st < 16; ++st) {
-            HEXI_SCHED_MFMA(1);
-            if (st + PFV < 16) HEXI_SCHED_DSREAD(2);
+            for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
+        m_run = NEG_BIG; l_run = 0.f; lr_run = 0.f;
+        thr_raw = NEG_BIG;   // any finite score exceeds it: the first visible tile always sets the maximum
+        if (NT == 0) return;
+        // prologue: group 1 requests K(0..3), group 0 requests V(0..1)
+        {
+            const int n_pre = grp ? K_AHEAD : V_AHEAD;
+            for (int j = 0; j < n_pre && j < NT; ++j) fetch_tile(j);
         }
+        if (grp == 1) {   // K(0) complete before anyone's M(0)
+            wait_vm((NT < K_AHEAD ? NT : K_AHEAD) - 1);
+            wg_barrier();
+        }
+        // before M(t): group 0 has requested V up to min(t + 1, NT - 1) and needs V(t - 1) complete
+        auto enter_m = [&](int t) __attribute__((always_inline)) {
+            if (grp == 0) wait_vm(NT - t < 2 ? NT - t : 2);
+            wg_barrier();
+        };
+        // before V(t): group 1 has requested K up to min(t + 3, NT - 1) and needs K(t + 1) complete; then the
+        // vector phase itself, starting with this group's share of the fetches
+        auto vector_part = [&](int t, auto first_c) __attribute__((always_inline)) {
+            if (grp == 1 && t + 1 < NT) wait_vm(NT - 2 - t < 2 ? NT - 2 - t : 2);
+            wg_barrier();
+            const int j = t + (grp ? K_AHEAD : V_AHEAD);
+            if (j < NT) fetch_tile(j);
+            if (t >= n_full_g) v_phase(t & (2 * NB - 1), first_c, std::true_type{}, exact);
+            else v_phase(t & (2 * NB - 1), first_c, std::false_type{}, exact);
+        };
+        enter_m(0);
+        m_phase(IC<0>{}, IC<16>{}, IC<32>{});
+        vector_part(0, std::true_type{});
+        // tiles 1 .. NT-1: four at a time in a straight line (buffer = t % 4 is then a compile-time constant and
+        // no accumulator passes through a control-flow merge), then the remaining ones through a switch
+        int t = 1;
+        for (; t + 3 < NT; t += 4) {
+            enter_m(t);     m_phase(IC<1>{}, IC<0>{}, IC<32>{}); vector_part(t, std::false_type{});
+            enter_m(t + 1); m_phase(IC<2>{}, IC<0>{}, IC<32>{}); vector_part(t + 1, std::false_type{});
+            enter_m(t + 2); m_phase(IC<3>{}, IC<0>{}, IC<32>{}); vector_part(t + 2, std::false_type{});
+            enter_m(t + 3); m_phase(IC<0>{}, IC<0>{}, IC<32>{}); vector_part(t + 3, std::false_type{});
+        }
+        for (; t < NT; ++t) {
+            enter_m(t);
+            switch (t & 3) {
+                case 0: m_phase(IC<0>{}, IC<0>{}, IC<32>{}); break;
+                case 1: m_phase(IC<1>{}, IC<0>{}, IC<32>{}); break;
+                case 2: m_phase(IC<2>{}, IC<0>{}, IC<32>{}); break;
+                default: m_phase(IC<3>{}, IC<0>{}, IC<32>{}); break;
+            }
+            vector_part(t, std::false_type{});
+        }
+        enter_m(NT);
+        switch (NT & 3) {
+            case 0: m_phase(IC<0>{}, IC<0>{}, IC<16>{}); break;
+            case 1: m_phase(IC<1>{}, IC<0>{}, IC<16>{}); break;
+            case 2: m_phase(IC<2>{}, IC<0>{}, IC<16>{}); break;
+            default: m_phase(IC<3>{}, IC<0>{}, IC<16>{}); break;
+        }
+        if (grp == 0) wg_barrier();
+    };
+
+    float l_tot, lr_tot;
+    for (int pass = 0; pass < 2; ++pass) {   // pass 1 (exact online softmax) only if a row of pass 0 left the safe range
+        run(pass == 1);
+        l_tot = sum_across_halves(l_run);
+        lr_tot = sum_across_halves(lr_run);
+        // a row that sees any key of the chunk sees its first key
+        const bool sees = my_row < g.lq && my_pos >= g.ks.start[0];
+        const int bad = pass == 0 && sees && !(l_tot >= SUM_LO && l_tot <= SUM_HI);
+        if (!__syncthreads_or(bad)) break;
     }
 
-#ifdef EXP_TIMING
-    asm volatile("s_nop 0" :: "v"(oacc[0][0]), "v"(oacc[3][15]));
-    TICK(0)
-    if (tid == 0) { for (int i = 0; i < 6; ++i) a.o[(long long)unit * 8 + i] = (float)tacc[i]; a.o[(long long)unit * 8 + 6] = (float)n_tiles; }
-    return;
-#endif
-    const float l_tot = sum_across_halves(l_run);
-    const float lr_tot = sum_across_halves(lr_run);
+    // Epilogue.  Every lane scales its row's O^T registers and merges the LSE; the scaled rows go through
+    // LDS (free now; a private 32 x 132-float region per wavefront, padded against bank conflicts) so that
+    // the global accesses are row-contiguous: one instruction covers two whole 512-byte rows of o.
     float inv = 0.f, lse_new = -INFINITY;
     if (l_tot > 0.f) {
         inv = lr_tot > 0.f ? 1.0f / lr_tot : 0.f;
         lse_new = (m_run + __log2f(l_tot)) * LN2;
     }
-    if (my_row >= g.lq) return;
-    float* op = a.o + ((long long)my_row * g.nq + h) * D + 4 * hh;
-    float* lp = a.lse + (long long)h * g.lq + my_row;
     float wa = 0.f, wb = inv;
+    float* lp = a.lse + (long long)h * g.lq + my_row_c;
     if (a.accumulate) {
         const float la = *lp;
         const float m = fmaxf(la, lse_new);
@@ -315,27 +426,49 @@ __global__ void __launch_bounds__(256, 2) fwd_bf16_kernel(const FwdArgs a, const
             lse_new = m + __logf(ea + eb);
         }
     }
+    float* stage = reinterpret_cast<float*>(&sm) + wave * (32 * O_STAGE_STRIDE + 32);
+    float* stage_wa = stage + 32 * O_STAGE_STRIDE;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            float4* dst = reinterpret_cast<float4*>(op + 32 * db + 8 * b);
-            float4 r = make_float4(oacc[db][4 * b] * wb, oacc[db][4 * b + 1] * wb, oacc[db][4 * b + 2] * wb, oacc[db][4 * b + 3] * wb);
-            if (a.accumulate) {
-                const float4 old = *dst;
-                r.x += wa * old.x; r.y += wa * old.y; r.z += wa * old.z; r.w += wa * old.w;
-            }
-            *dst = r;
-        }
-    // both half-wave lanes of a row read *lp in the same instruction above, before this write
-    if (hh == 0) *lp = lse_new;
+        for (int b = 0; b < 4; ++b)
+            *reinterpret_cast<float4*>(&stage[l32 * O_STAGE_STRIDE + 32 * db + 8 * b + 4 * hh]) =
+                make_float4(oacc[db][4 * b] * wb, oacc[db][4 * b + 1] * wb, oacc[db][4 * b + 2] * wb, oacc[db][4 * b + 3] * wb);
+    if (hh == 0) {
+        stage_wa[l32] = wa;
+        if (my_row < g.lq) *lp = lse_new;   // both half-wave lanes of a row read *lp above, in the same instruction
+    }
+    // the region is private to the wavefront: its own LDS writes only need to have completed
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int wrow0 = grow0 + 32 * wg;
+    float* obase = a.o + ((long long)wrow0 * g.nq + h) * D + 4 * l32;
+    const long long row_stride = (long long)g.nq * D;
+    float4 val[16];
+    float4 old[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int r = 2 * i + hh;
+        val[i] = *reinterpret_cast<const float4*>(&stage[r * O_STAGE_STRIDE + 4 * l32]);
+        if (a.accumulate && wrow0 + r < g.lq) old[i] = *reinterpret_cast<const float4*>(obase + r * row_stride);
+        else old[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int r = 2 * i + hh;
+        const float w = stage_wa[r];
+        float4 o4 = val[i];
+        o4.x += w * old[i].x; o4.y += w * old[i].y; o4.z += w * old[i].z; o4.w += w * old[i].w;
+        if (wrow0 + r < g.lq) *reinterpret_cast<float4*>(obase + r * row_stride) = o4;
+    }
 }
 
 }  // namespace
 
 hipError_t hexi_launch_fwd_bf16(const FwdArgs& a, hipStream_t s)
 {
-    const int n_q_tiles = (a.g.lq + TM - 1) / TM;
-    fwd_bf16_kernel<<<(unsigned)(a.g.nq * n_q_tiles), 256, 0, s>>>(a, n_q_tiles);
+    const int n_q_tiles = (a.g.lq + WG_ROWS - 1) / WG_ROWS;
+    fwd_bf16_kernel<<<(unsigned)(a.g.nq * n_q_tiles), 512, 0, s>>>(a, n_q_tiles);
     return hipGetLastError();
 }

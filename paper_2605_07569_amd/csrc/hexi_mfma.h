@@ -67,6 +67,19 @@ __device__ __forceinline__ bf16x8 pack_bf16x8_sum(float a0, float a1, float a2, 
     return r;
 }
 
+// Same with four independent running sums (one per pair), so that the additions do not form one chain.
+__device__ __forceinline__ bf16x8 pack_bf16x8_sum4(float a0, float a1, float a2, float a3, float a4, float a5, float a6, float a7, float (&sum)[4])
+{
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    const bf16x2 t0 = {(__bf16)a0, (__bf16)a1}, t1 = {(__bf16)a2, (__bf16)a3}, t2 = {(__bf16)a4, (__bf16)a5}, t3 = {(__bf16)a6, (__bf16)a7};
+    sum[0] = __builtin_amdgcn_fdot2_f32_bf16(t0, ones, sum[0], false);
+    sum[1] = __builtin_amdgcn_fdot2_f32_bf16(t1, ones, sum[1], false);
+    sum[2] = __builtin_amdgcn_fdot2_f32_bf16(t2, ones, sum[2], false);
+    sum[3] = __builtin_amdgcn_fdot2_f32_bf16(t3, ones, sum[3], false);
+    bf16x8 r = {t0[0], t0[1], t1[0], t1[1], t2[0], t2[1], t3[0], t3[1]};
+    return r;
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // Direct global->LDS load (LDS DMA): every lane supplies its own global address; the 64 lanes' 16-byte
@@ -78,9 +91,42 @@ __device__ __forceinline__ void lds_dma16(const void* gptr, uint32_t lds_addr)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
 }
+// Same with a wave-uniform 64-bit base in SGPRs and a 32-bit per-lane byte offset.
+__device__ __forceinline__ void lds_dma16_base(const void* base, uint32_t byte_off, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(byte_off), "s"(base) : "memory");
+}
 __device__ __forceinline__ void lds_dma4(const void* gptr, uint32_t lds_addr)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_addr), "v"(gptr) : "memory");
+}
+
+// LDS reads issued through inline assembly with a compile-time offset field, for software pipelines whose
+// address registers must stay exactly the ones the kernel computed (the compiler otherwise materialises
+// one address register per buffer).  The compiler does not see these reads: the destination is valid
+// only after the matching lds_wait<N>(), which waits until at most N younger LDS operations of the
+// wavefront are outstanding and ties the destination registers to the wait, so that no consumer (and no
+// register copy) can be scheduled before it.
+template <int OFF> __device__ __forceinline__ void lds_issue_b128(bf16x8& r, uint32_t addr)
+{
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+}
+template <int OFF> __device__ __forceinline__ void lds_issue_tr16(s16x4& r, uint32_t addr)
+{
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+}
+template <int N> __device__ __forceinline__ void lds_wait(bf16x8& r)
+{
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(r) : "n"(N));
+}
+template <int N> __device__ __forceinline__ void lds_wait(s16x4& a, s16x4& b)
+{
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(N));
+}
+__device__ __forceinline__ bf16x8 join_halves(s16x4 x, s16x4 y)
+{
+    s16x8 r = {x[0], x[1], x[2], x[3], y[0], y[1], y[2], y[3]};
+    return __builtin_bit_cast(bf16x8, r);
 }
 
 // fp32 atomic add to global memory without a return value (global_atomic_add_f32)
