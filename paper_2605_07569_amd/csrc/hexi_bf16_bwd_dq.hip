@@ -1,40 +1,54 @@
-// bf16 backward ring step, dQ part, for gfx950: one workgroup (4 wavefronts) per (128-row q tile,
-// q head); the q tile's dQ stays in accumulators while the chunk's keys stream past, so dQ needs no
-// atomics and its summation order is fixed.
+// bf16 backward ring step, dQ part, for gfx950: one workgroup of 8 wavefronts per (256-row q tile, q head),
+// one workgroup per CU; the q tile's dQ stays in accumulators while the chunk's keys stream past, so dQ needs
+// no atomics and its summation order is fixed.
 //
-// Everything is computed transposed, as in the forward kernel, so that every lane owns one query
-// row and the row constants (saved global LSE, Delta) are per-lane scalars:
+// Everything is computed transposed, as in the forward kernel, so that every lane owns one query row and the
+// row constants (saved global LSE, Delta) are per-lane scalars:
 //   S^T = K Q^T,  dP^T = V dO^T  (K, V rows read from LDS with 128-bit reads; Q^T, dO^T in registers),
 //   P^T = exp2(S^T * scale*log2e - LSE*log2e),  dS^T = P^T (dP^T - Delta),
 //   dQ^T += K^T dS^T  (K^T through transposed LDS reads; dS^T straight from the accumulator registers).
-// K / V tiles (64 keys) are double-buffered in LDS and fetched one tile ahead with direct global->LDS
-// loads, XOR-swizzled, one barrier per tile.  At the end dq_acc += scale * dQ (plain read-modify-write:
-// each (row, head) belongs to exactly one workgroup of the launch).
+//
+// Ping-pong schedule (see the forward kernel): two groups of four wavefronts, wavefront w and w + 4 on one
+// SIMD, alternate between a matrix phase and a vector phase with one workgroup barrier per phase, group 1 one
+// phase behind group 0, so that every SIMD always has one wavefront issuing only MFMAs (and their LDS reads)
+// and one issuing only VALU work.  A phase covers a 32-key block (half a 64-key LDS tile), which keeps the
+// scores and dP of one block only in registers:
+//   M(b): dQ^T += K^T dS^T of block b-1 (8 MFMAs), then S^T and dP^T of block b (16 MFMAs);
+//   V(b): P^T and dS^T of block b, dS^T rounded to bf16 operand slots.
+// The vector-phase group also issues the direct global->LDS loads: during the first block of tile j, group 1
+// requests K of tile j + 3 and group 0 requests V of tile j + 3 (four LDS buffers per tensor).
 #include "hexi_internal.h"
 #include "hexi_mfma.h"
-#include <type_traits>
 
 namespace {
 
 constexpr int D = 128;
-constexpr int TM = 128;          // q rows per workgroup (32 per wavefront)
-constexpr int TN = 64;           // keys per tile
+constexpr int TN = 64;             // keys per LDS tile (two 32-key blocks)
+constexpr int NB = 4;              // LDS buffers per tensor
+constexpr int GROUP_ROWS = 128;    // q rows per wavefront group (32 per wavefront)
+constexpr int WG_ROWS = 256;       // q rows per workgroup
+constexpr int AHEAD = 3;           // tile j + 3 is requested during tile j
+constexpr int DMA_PER_WAVE = 5;    // transfers per wavefront per tile (17 real ones per tile, 3 dummies)
+constexpr int STAGE_STRIDE = D + 4;   // floats per staged output row (epilogue)
 constexpr float LOG2E = 1.4426950408889634f;
 
-__device__ __forceinline__ int swz_row(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
-
 struct DqSmem {
-    uint16_t k[2][TN * D];   // 2 x 16 KB
-    uint16_t v[2][TN * D];   // 2 x 16 KB
-    int kpos[2][TN];
+    unsigned char k[NB][P16_TILE_BYTES];   // 4 x 17 KB
+    unsigned char v[NB][P16_TILE_BYTES];   // 4 x 17 KB
+    int kpos[2 * NB][TN];     // key positions of the tiles that need a mask, written AHEAD tiles ahead
+    unsigned char dump[1024]; // destination of the dummy transfers
+    // the epilogue stages 8 x (32 x 132) floats over the start of this struct
 };
+static_assert(sizeof(DqSmem) >= 8 * 32 * STAGE_STRIDE * 4, "epilogue staging does not fit");
 
-__global__ void __launch_bounds__(256, 2) bwd_dq_bf16_kernel(const BwdArgs a, const int n_q_tiles)
+__global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const int n_q_tiles)
 {
     const AttnGeom& g = a.g;
     __shared__ __attribute__((aligned(1024))) DqSmem sm;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = wave >> 2, wg = wave & 3;
     const int l32 = lane & 31, hh = lane >> 5;
     const int grp2 = (lane >> 4) & 1, j16 = lane & 15;
 
@@ -49,24 +63,27 @@ __global__ void __launch_bounds__(256, 2) bwd_dq_bf16_kernel(const BwdArgs a, co
     const int h = unit / n_q_tiles;
     const int q_tile = n_q_tiles - 1 - (unit - h * n_q_tiles);
     const int kvh = g.kv_of_q[h];
-    const int row0 = q_tile * TM;
-    const int my_row = row0 + 32 * wave + l32;
+    const int row0 = q_tile * WG_ROWS;
+    const int grow0 = row0 + GROUP_ROWS * grp;
+    const int my_row = grow0 + 32 * wg + l32;
     const int my_row_c = my_row < g.lq ? my_row : g.lq - 1;
     const int my_pos = my_row < g.lq ? seg_pos_of_row(g.qs, my_row) : -1;
 
     const uint16_t* k = static_cast<const uint16_t*>(a.k) + (long long)kvh * g.kv_stride_head;
     const uint16_t* v = static_cast<const uint16_t*>(a.v) + (long long)kvh * g.kv_stride_head;
 
-    const int last_row = (row0 + TM < g.lq ? row0 + TM : g.lq) - 1;
-    const int n_vis = seg_rows_le(g.ks, seg_pos_of_row(g.qs, last_row));
-    const int n_all = seg_rows_le(g.ks, seg_pos_of_row(g.qs, row0));
-    const int n_tiles = (n_vis + TN - 1) / TN;
-    const int n_full_tiles = n_all / TN;
-    if (n_tiles == 0) return;     // this q tile sees nothing of the chunk: dq_acc unchanged
+    // n_full_g: tiles this group needs no mask for; NT: tiles the workgroup streams (those visible to its last
+    // rows; a group whose rows see fewer masks the rest away); n_full_wg: tiles no row needs a mask for.
+    int n_full_g = 0;
+    if (grow0 < g.lq) n_full_g = seg_rows_le(g.ks, seg_pos_of_row(g.qs, grow0)) / TN;
+    const int wg_last_row = (row0 + WG_ROWS < g.lq ? row0 + WG_ROWS : g.lq) - 1;
+    const int NT = (seg_rows_le(g.ks, seg_pos_of_row(g.qs, wg_last_row)) + TN - 1) / TN;
+    const int n_full_wg = seg_rows_le(g.ks, seg_pos_of_row(g.qs, row0)) / TN;
+    if (NT == 0) return;     // this q tile sees nothing of the chunk: dq_acc unchanged
 
     // Q^T and dO^T operand fragments: lane (row l32, half hh) holds d = 16*ks + 8*hh .. +7
     bf16x8 qf[8], gf[8];
-    float lse2, delta;
+    float neg_lse2, delta;
     {
         const long long off = (long long)my_row_c * g.q_stride_tok + (long long)h * g.q_stride_head + 8 * hh;
         const uint16_t* qp = static_cast<const uint16_t*>(a.q) + off;
@@ -78,196 +95,256 @@ __global__ void __launch_bounds__(256, 2) bwd_dq_bf16_kernel(const BwdArgs a, co
         }
         const float l = a.lse[(long long)h * g.lq + my_row_c];
         // rows that see nothing anywhere (LSE = -inf) and padding rows: P = 0 through LSE = +inf
-        lse2 = (my_row < g.lq && l != -INFINITY) ? l * LOG2E : INFINITY;
+        neg_lse2 = (my_row < g.lq && l != -INFINITY) ? -l * LOG2E : -INFINITY;
         delta = a.delta[(long long)h * g.lq + my_row_c];
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) { pin(qf[ks]); pin(gf[ks]); }
-        asm volatile("" ::"v"(lse2), "v"(delta));
+        asm volatile("" ::"v"(neg_lse2), "v"(delta));
     }
 
-    int fetch_off[4];
+    // Direct global->LDS fetch of one tile by the four wavefronts of a group (group 1: K, group 0: V).  A
+    // transfer is one wave-wide instruction: lane L writes the 16 bytes at (transfer * 1024 + 16 * L) of the
+    // tile's LDS image and reads the 16-byte piece of the key row that belongs there (the pad piece re-reads
+    // piece 0).  Wavefront wg issues transfers wg, wg + 4, ..., wg + 16; transfer numbers past the tile's end
+    // go to a dump area.
+    constexpr int N_XFER = P16_TILE_BYTES / 1024;
+    uint32_t fetch_off[DMA_PER_WAVE];   // byte offsets from the tile's first key
+    int fetch_row[DMA_PER_WAVE];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int r = (wave * 4 + i) * 4 + (lane >> 4);
-        fetch_off[i] = r * (int)g.kv_stride_tok + (((lane & 15) ^ swz_row(r)) << 3);
+    for (int i = 0; i < DMA_PER_WAVE; ++i) {
+        const int pos = (wg + 4 * i) * 1024 + 16 * lane;
+        int r = pos / P16_ROW_BYTES, c = (pos - r * P16_ROW_BYTES) >> 4;
+        r = p16_row(r);     // the permutation is its own inverse: LDS row -> key
+        if (wg + 4 * i >= N_XFER) r = 0;
+        if (c >= 16) c = 0;
+        fetch_row[i] = r;
+        fetch_off[i] = 2u * (uint32_t)(r * (int)g.kv_stride_tok + c * 8);
     }
     const uint32_t lds_k = (uint32_t)(uintptr_t)(&sm.k[0][0]), lds_v = (uint32_t)(uintptr_t)(&sm.v[0][0]);
-    auto fetch_tile = [&](int tile, int buf) {
+    const uint32_t lds_dump = (uint32_t)(uintptr_t)(&sm.dump[0]);
+    const uint16_t* fetch_src = grp ? k : v;
+    const uint32_t fetch_lds = grp ? lds_k : lds_v;
+    auto fetch_tile = [&](int tile) {
         const int col0 = tile * TN;
-        const uint32_t wk = __builtin_amdgcn_readfirstlane(lds_k + buf * (TN * D * 2) + wave * 4096);
-        const uint32_t wv = __builtin_amdgcn_readfirstlane(lds_v + buf * (TN * D * 2) + wave * 4096);
+        const uint32_t dst = __builtin_amdgcn_readfirstlane(fetch_lds + (tile & (NB - 1)) * P16_TILE_BYTES + wg * 1024);
+        const uint16_t* src = fetch_src + (long long)col0 * g.kv_stride_tok;
         if (col0 + TN <= g.lc) {
-            const uint16_t* kb = k + (long long)col0 * g.kv_stride_tok;
-            const uint16_t* vb = v + (long long)col0 * g.kv_stride_tok;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                lds_dma16(kb + fetch_off[i], wk + i * 1024);
-                lds_dma16(vb + fetch_off[i], wv + i * 1024);
+            for (int i = 0; i < DMA_PER_WAVE; ++i) {
+                const uint32_t d = wg + 4 * i < N_XFER ? dst + i * 4096 : lds_dump;
+                lds_dma16_base(src, fetch_off[i], __builtin_amdgcn_readfirstlane(d));
             }
         } else {   // ragged last tile: clamp the key index (the extra keys are masked through their position)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int r = (wave * 4 + i) * 4 + (lane >> 4);
-                const int c = (lane & 15) ^ swz_row(r);
-                const int col = col0 + r < g.lc ? col0 + r : g.lc - 1;
-                const long long off = (long long)col * g.kv_stride_tok + c * 8;
-                lds_dma16(k + off, wk + i * 1024);
-                lds_dma16(v + off, wv + i * 1024);
+            for (int i = 0; i < DMA_PER_WAVE; ++i) {
+                uint32_t off = fetch_off[i];
+                if (col0 + fetch_row[i] >= g.lc) off -= 2u * (uint32_t)((col0 + fetch_row[i] - (g.lc - 1)) * (int)g.kv_stride_tok);
+                const uint32_t d = wg + 4 * i < N_XFER ? dst + i * 4096 : lds_dump;
+                lds_dma16_base(src, off, __builtin_amdgcn_readfirstlane(d));
             }
         }
-        if (wave == 0 && tile >= n_full_tiles)
-            sm.kpos[buf][lane] = col0 + lane < g.lc ? seg_pos_of_row(g.ks, col0 + lane) : 0x7fffffff;
+        // global positions of the tile's keys, for the tiles some row needs a mask for
+        if (grp == 1 && wg == 0 && tile >= n_full_wg) {
+            sm.kpos[tile & (2 * NB - 1)][lane] = col0 + lane < g.lc ? seg_pos_of_row(g.ks, col0 + lane) : 0x7fffffff;
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
     };
+
+    // Lane parts of the LDS byte addresses; buffer, block and step are compile-time offsets of the reads.
+    //   row fragment (block b, ks) of buffer B:  nat_addr + B * TILE + 32 * b * ROW + 32 * ks     (K and V alike)
+    //   K^T fragment (16-key step u of the tile, 32-column block db, half `second`) of buffer B: keys
+    //   16u + 8*second + 4*hh + jj sit in LDS rows 16u + 4*jj + 2*second + hh:
+    //        ktr_addr[B / 2] + (B % 2) * TILE + (16 * u + 2 * second) * ROW + 64 * db
+    // (two base registers: the offset field of an LDS read holds 16 bits).
+    const int jj = j16 >> 2;
+    const uint32_t nat_lane = p16_row(l32) * P16_ROW_BYTES + 16 * hh;
+    const uint32_t knat_addr = lds_k + nat_lane, vnat_addr = lds_v + nat_lane;
+    uint32_t ktr_addr[2];
+    ktr_addr[0] = lds_k + (4 * jj + hh) * P16_ROW_BYTES + 2 * (16 * grp2 + 4 * (j16 & 3));
+    ktr_addr[1] = ktr_addr[0] + 2 * P16_TILE_BYTES;
 
     f32x16 dq[4];
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) dq[db][r] = 0.f;
+    f32x16 s, dp;
+    bf16x8 dsf[2];
     const float c_log2 = g.scale * LOG2E;
-    const float neg_lse2 = -lse2;
-    const int sw_l32 = swz_row(l32);
-    const int jj = j16 >> 2, cl = 2 * grp2 + ((j16 & 3) >> 1);
 
-    // Lane parts of the LDS addresses (elements); block, step and buffer are compile-time offsets.
-    int nat_lane[8], tr_lane[8];
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) nat_lane[ks] = l32 * D + (((2 * ks + hh) ^ sw_l32) << 3);
-#pragma unroll
-    for (int x = 0; x < 8; ++x) {   // x = 2*db + second
-        const int db = x >> 1, second = x & 1;
-        tr_lane[x] = (4 * hh + jj + 8 * second) * D + ((((db ^ jj) << 2) | (cl ^ (hh + 2 * second))) << 3) + 4 * (j16 & 1);
-    }
-
-    // One 64-key tile.  The two 32-key blocks are staggered so that the VALU work of one block sits between
-    // MFMAs of the other in program order:
-    //   A: S^T/dP^T(block 0) | B: S^T/dP^T(block 1) + VALU(block 0) | C: dQ^T(block 0) + VALU(block 1) | D: dQ^T(block 1)
-    // Every step ends in a scheduling barrier so that this interleave is what gets issued.
-    auto tile_body = [&](auto buf_c, auto masked_c) __attribute__((always_inline)) {
-        constexpr bool MASKED = decltype(masked_c)::value;
-        constexpr int buf = decltype(buf_c)::value;
-        const uint16_t* Ks = &sm.k[buf][0];
-        const uint16_t* Vs = &sm.v[buf][0];
-        f32x16 s[2], dp[2];
-        bf16x8 dsf[4];
-        constexpr int PF = 2;
-        bf16x8 ra[PF], rb_[PF];
-        auto load_nat = [&](int b, int ks, int slot) {
-            ra[slot] = *reinterpret_cast<const bf16x8*>(&Ks[nat_lane[ks] + 32 * b * D]);
-            rb_[slot] = *reinterpret_cast<const bf16x8*>(&Vs[nat_lane[ks] + 32 * b * D]);
-        };
-        // K^T fragment of 16-key step u (= 2*b + st/4... see callers) and 32-column block db
-        auto load_tr = [&](int u, int db, int slot) {
-            ra[slot] = lds_tr_pair(&Ks[tr_lane[2 * db] + 16 * u * D], &Ks[tr_lane[2 * db + 1] + 16 * u * D]);
-        };
-        auto valu2 = [&](int b, int e) {
-#pragma unroll
-            for (int x = e; x < e + 2; ++x) {
-                float p = fast_exp2(fmaf(s[b][x], c_log2, neg_lse2));
-                if (MASKED) p = (sm.kpos[buf][32 * b + 8 * (x >> 2) + 4 * hh + (x & 3)] > my_pos) ? 0.f : p;
-                dp[b][x] = p * (dp[b][x] - delta);
+    // Matrix phase of block (tile buffer B, half HALF).  Steps 0..7: dQ^T += K^T dS^T of the previous block
+    // (two 16-key steps x four 32-column blocks; the previous block is the other half of the same tile, or
+    // the second half of the tile before).  Steps 8..23: S^T and dP^T of this block, alternating.
+    // [FIRST, LAST) selects the steps; operand fragments are requested PF steps ahead.
+    auto m_phase = [&](auto bc, auto half_c, auto first_c, auto last_c) __attribute__((always_inline)) {
+        constexpr int B = decltype(bc)::value, HALF = decltype(half_c)::value;
+        constexpr int FIRST = decltype(first_c)::value, LAST = decltype(last_c)::value;
+        constexpr int PF = 4, NS = PF + 1;   // a fragment's registers are busy from its request until its MFMA
+        constexpr int BP = HALF ? B : (B + NB - 1) % NB;     // buffer of the previous block
+        constexpr int UP = HALF ? 0 : 2;                      // its first 16-key step within that tile
+        s16x4 ta[NS], tb[NS];
+        bf16x8 nb[NS];
+        auto issue = [&](auto stc) __attribute__((always_inline)) {
+            constexpr int st = decltype(stc)::value, slot = (st - FIRST) % NS;
+            if constexpr (st < 8) {
+                constexpr int u = UP + (st >> 2), db = st & 3;
+                constexpr int off = (BP % 2) * P16_TILE_BYTES + 16 * u * P16_ROW_BYTES + 64 * db;
+                lds_issue_tr16<off>(ta[slot], ktr_addr[BP / 2]);
+                lds_issue_tr16<off + 2 * P16_ROW_BYTES>(tb[slot], ktr_addr[BP / 2]);
+            } else {
+                constexpr int ks = (st - 8) >> 1;
+                constexpr int off = B * P16_TILE_BYTES + 32 * HALF * P16_ROW_BYTES + 32 * ks;
+                if constexpr (((st - 8) & 1) == 0) lds_issue_b128<off>(nb[slot], knat_addr);
+                else lds_issue_b128<off>(nb[slot], vnat_addr);
             }
         };
-        auto pack = [&](int b, int half) {
-            const int x = 8 * half;
-            dsf[2 * b + half] = pack_bf16x8(dp[b][x], dp[b][x + 1], dp[b][x + 2], dp[b][x + 3], dp[b][x + 4], dp[b][x + 5], dp[b][x + 6], dp[b][x + 7]);
+        auto step = [&](auto stc) __attribute__((always_inline)) {
+            constexpr int st = decltype(stc)::value, slot = (st - FIRST) % NS;
+            if constexpr (st + PF < LAST) issue(IC<st + PF>{});
+            // LDS reads younger than this step's fragment: those of the next PF steps that exist
+            constexpr int hi = st + PF < LAST ? st + PF : LAST - 1;
+            constexpr int n_tr = (hi < 8 ? hi : 7) - (st < 8 ? st : 7);      // steps in (st, hi] below 8
+            constexpr int younger = 2 * n_tr + ((hi - st) - n_tr);
+            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            if constexpr (st < 8) {
+                lds_wait<younger>(ta[slot], tb[slot]);
+                dq[st & 3] = mfma32(join_halves(ta[slot], tb[slot]), dsf[st >> 2], dq[st & 3]);
+            } else {
+                constexpr int ks = (st - 8) >> 1;
+                lds_wait<younger>(nb[slot]);
+                if constexpr (((st - 8) & 1) == 0) s = mfma32(nb[slot], qf[ks], ks == 0 ? zero : s);
+                else dp = mfma32(nb[slot], gf[ks], ks == 0 ? zero : dp);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         };
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) { s[b][r] = 0.f; dp[b][r] = 0.f; }
-        // phase A (global steps 0..7)
-#pragma unroll
-        for (int ks = 0; ks < PF; ++ks) load_nat(0, ks, ks);
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 kf = ra[ks % PF], vf = rb_[ks % PF];
-            if (ks + PF < 8) load_nat(0, ks + PF, ks % PF);
-            else load_nat(1, ks + PF - 8, ks % PF);
-            s[0] = mfma32(kf, qf[ks], s[0]);
-            dp[0] = mfma32(vf, gf[ks], dp[0]);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        // phase B (global steps 8..15): block 1 products, block 0 VALU
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 kf = ra[(8 + ks) % PF], vf = rb_[(8 + ks) % PF];
-            if (ks + PF < 8) load_nat(1, ks + PF, (8 + ks) % PF);
-            else load_tr((ks + PF - 8) >> 2, (ks + PF - 8) & 3, (8 + ks) % PF);
-            s[1] = mfma32(kf, qf[ks], s[1]);
-            dp[1] = mfma32(vf, gf[ks], dp[1]);
-            valu2(0, 2 * ks);
-            if (ks == 4) pack(0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        pack(0, 1);
-        // phase C (global steps 16..23): dQ^T += K^T dS^T for 16-key steps 0,1 (block 0); block 1 VALU
-#pragma unroll
-        for (int st = 0; st < 8; ++st) {
-            const bf16x8 kt = ra[(16 + st) % PF];
-            if (st + PF < 8) load_tr((st + PF) >> 2, (st + PF) & 3, (16 + st) % PF);
-            else load_tr(2 + ((st + PF - 8) >> 2), (st + PF - 8) & 3, (16 + st) % PF);
-            dq[st & 3] = mfma32(kt, dsf[st >> 2], dq[st & 3]);
-            valu2(1, 4 * (st >> 1) + 2 * (st & 1));
-            if (st == 4) pack(1, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        pack(1, 1);
-        // phase D (global steps 24..31): 16-key steps 2,3 (block 1)
-#pragma unroll
-        for (int st = 0; st < 8; ++st) {
-            const bf16x8 kt = ra[(24 + st) % PF];
-            if (st + PF < 8) load_tr(2 + ((st + PF) >> 2), (st + PF) & 3, (24 + st) % PF);
-            dq[st & 3] = mfma32(kt, dsf[2 + (st >> 2)], dq[st & 3]);
-            __builtin_amdgcn_sched_barrier(0);
-        }
+        __builtin_amdgcn_sched_barrier(0);
+        for_range<FIRST, (FIRST + PF < LAST ? FIRST + PF : LAST)>(issue);
+        for_range<FIRST, LAST>(step);
     };
 
-    fetch_tile(0, 0);
-    // one tile: publish it (wait for this wavefront's outstanding global->LDS loads, then barrier), start
-    // fetching the next one into the other buffer, compute
-    auto step = [&](int tile, auto buf_c, auto masked_c) __attribute__((always_inline)) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (tile + 1 < n_tiles) fetch_tile(tile + 1, decltype(buf_c)::value ^ 1);
-        tile_body(buf_c, masked_c);
+    // Vector phase of a block: P^T = exp2(S^T c - LSE log2e), dS^T = P^T (dP^T - Delta), rounded to bf16
+    // operand slots.  MASKED: the tile needs the causal mask (key positions from LDS).
+    auto v_phase = [&](int kpos_slot, int half, auto masked_c) __attribute__((always_inline)) {
+        constexpr bool MASKED = decltype(masked_c)::value;
+        float ds[16];
+#pragma unroll
+        for (int x = 0; x < 16; ++x) {
+            const float p = fast_exp2(fmaf(s[x], c_log2, neg_lse2));
+            ds[x] = p * (dp[x] - delta);
+        }
+        if (MASKED) {
+            const int* kp = &sm.kpos[kpos_slot][32 * half];
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb) {
+                const int4 p4 = *reinterpret_cast<const int4*>(&kp[8 * rb + 4 * hh]);
+                if (p4.x > my_pos) ds[4 * rb] = 0.f;
+                if (p4.y > my_pos) ds[4 * rb + 1] = 0.f;
+                if (p4.z > my_pos) ds[4 * rb + 2] = 0.f;
+                if (p4.w > my_pos) ds[4 * rb + 3] = 0.f;
+            }
+        }
+        dsf[0] = pack_bf16x8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
+        dsf[1] = pack_bf16x8(ds[8], ds[9], ds[10], ds[11], ds[12], ds[13], ds[14], ds[15]);
+        // keep the whole vector phase on this side of the next barrier
+        asm volatile("" : "+v"(dsf[0]), "+v"(dsf[1]));
     };
-    using B0 = std::integral_constant<int, 0>;
-    using B1 = std::integral_constant<int, 1>;
-    // unmasked tiles two at a time, then the masked tail (buffer = tile parity throughout)
-    int tile = 0;
-    for (; tile + 1 < n_full_tiles; tile += 2) {
-        step(tile, B0{}, std::false_type{});
-        step(tile + 1, B1{}, std::false_type{});
-    }
-    if (tile < n_full_tiles) { step(tile, B0{}, std::false_type{}); ++tile; }
-    if (tile < n_tiles && (tile & 1)) { step(tile, B1{}, std::true_type{}); ++tile; }
-    for (; tile + 1 < n_tiles; tile += 2) {
-        step(tile, B0{}, std::true_type{});
-        step(tile + 1, B1{}, std::true_type{});
-    }
-    if (tile < n_tiles) step(tile, B0{}, std::true_type{});
 
-    if (my_row >= g.lq) return;
-    // lane (row l32, half hh): register 4*b + t of block db holds d = 32*db + 8*b + 4*hh + t
-    float* dst0 = a.dq + ((long long)my_row * g.nq + h) * D + 4 * hh;
+    // Phase sequence of a group: M(0) V(0) M(1) V(1) ... M(2 NT) over the 2 NT blocks, a barrier before every
+    // phase; group 1 starts one barrier late and group 0 ends with one extra.  Tile j must have landed before
+    // group 0 enters M of its first block: group 0 (V) waits there, group 1 (K) waits before the vector phase
+    // it runs in that same slot, V(2j - 1).  At that point tiles up to min(j + 2, NT - 1) have been requested.
+    auto need_tile = [&](int j) __attribute__((always_inline)) {
+        if (j < NT) wait_tiles_in_flight((j + 2 < NT - 1 ? j + 2 : NT - 1) - j);
+    };
+    auto enter_m = [&](int blk) __attribute__((always_inline)) {
+        if (grp == 0 && (blk & 1) == 0) need_tile(blk >> 1);
+        wg_barrier();
+    };
+    auto vector_part = [&](int blk) __attribute__((always_inline)) {
+        if (grp == 1 && (blk & 1) == 1) need_tile((blk + 1) >> 1);
+        wg_barrier();
+        const int t = blk >> 1;
+        if ((blk & 1) == 0 && t + AHEAD < NT) fetch_tile(t + AHEAD);
+        if (t >= n_full_g) v_phase(t & (2 * NB - 1), blk & 1, std::true_type{});
+        else v_phase(t & (2 * NB - 1), blk & 1, std::false_type{});
+    };
+
+    for (int j = 0; j < AHEAD && j < NT; ++j) fetch_tile(j);
+    if (grp == 1) {   // K(0) complete before anyone's M(0)
+        need_tile(0);
+        wg_barrier();
+    }
+    enter_m(0); m_phase(IC<0>{}, IC<0>{}, IC<8>{}, IC<24>{}); vector_part(0);
+    enter_m(1); m_phase(IC<0>{}, IC<1>{}, IC<0>{}, IC<24>{}); vector_part(1);
+    // tiles 1 .. NT-1: four at a time in a straight line (buffer = t % 4 is then a compile-time constant and no
+    // accumulator passes through a control-flow merge), then the remaining ones through a switch
+    auto tile_steps = [&](int t, auto bc) __attribute__((always_inline)) {
+        enter_m(2 * t);     m_phase(bc, IC<0>{}, IC<0>{}, IC<24>{}); vector_part(2 * t);
+        enter_m(2 * t + 1); m_phase(bc, IC<1>{}, IC<0>{}, IC<24>{}); vector_part(2 * t + 1);
+    };
+    int t = 1;
+    for (; t + 3 < NT; t += 4) {
+        tile_steps(t, IC<1>{});
+        tile_steps(t + 1, IC<2>{});
+        tile_steps(t + 2, IC<3>{});
+        tile_steps(t + 3, IC<0>{});
+    }
+    for (; t < NT; ++t) {
+        switch (t & 3) {
+            case 0: tile_steps(t, IC<0>{}); break;
+            case 1: tile_steps(t, IC<1>{}); break;
+            case 2: tile_steps(t, IC<2>{}); break;
+            default: tile_steps(t, IC<3>{}); break;
+        }
+    }
+    enter_m(2 * NT);
+    switch (NT & 3) {
+        case 0: m_phase(IC<0>{}, IC<0>{}, IC<0>{}, IC<8>{}); break;
+        case 1: m_phase(IC<1>{}, IC<0>{}, IC<0>{}, IC<8>{}); break;
+        case 2: m_phase(IC<2>{}, IC<0>{}, IC<0>{}, IC<8>{}); break;
+        default: m_phase(IC<3>{}, IC<0>{}, IC<0>{}, IC<8>{}); break;
+    }
+    if (grp == 0) wg_barrier();
+    __syncthreads();   // every wavefront is done with the tiles: LDS is free for the epilogue
+
+    // Epilogue: dq_acc += scale * dQ.  The scaled rows go through LDS (a private 32 x 132-float region per
+    // wavefront, padded against bank conflicts) so that the global read-modify-write is row-contiguous: one
+    // instruction covers two whole 512-byte rows.  Each (row, head) belongs to exactly one workgroup.
+    float* stage = reinterpret_cast<float*>(&sm) + wave * (32 * STAGE_STRIDE);
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            float4* dst = reinterpret_cast<float4*>(dst0 + 32 * db + 8 * b);
-            float4 o = *dst;
-            o.x += g.scale * dq[db][4 * b]; o.y += g.scale * dq[db][4 * b + 1];
-            o.z += g.scale * dq[db][4 * b + 2]; o.w += g.scale * dq[db][4 * b + 3];
-            *dst = o;
-        }
+        for (int b = 0; b < 4; ++b)
+            *reinterpret_cast<float4*>(&stage[l32 * STAGE_STRIDE + 32 * db + 8 * b + 4 * hh]) =
+                make_float4(dq[db][4 * b] * g.scale, dq[db][4 * b + 1] * g.scale, dq[db][4 * b + 2] * g.scale, dq[db][4 * b + 3] * g.scale);
+    // the region is private to the wavefront: its own LDS writes only need to have completed
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int wrow0 = grow0 + 32 * wg;
+    float* obase = a.dq + ((long long)wrow0 * g.nq + h) * D + 4 * l32;
+    const long long row_stride = (long long)g.nq * D;
+    float4 old[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int r = 2 * i + hh;
+        old[i] = wrow0 + r < g.lq ? *reinterpret_cast<const float4*>(obase + r * row_stride) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int r = 2 * i + hh;
+        const float4 val = *reinterpret_cast<const float4*>(&stage[r * STAGE_STRIDE + 4 * l32]);
+        float4 o4 = old[i];
+        o4.x += val.x; o4.y += val.y; o4.z += val.z; o4.w += val.w;
+        if (wrow0 + r < g.lq) *reinterpret_cast<float4*>(obase + r * row_stride) = o4;
+    }
 }
 
 }  // namespace
 
 hipError_t hexi_launch_bwd_dq_bf16(const BwdArgs& a, hipStream_t s)
 {
-    const int n_q_tiles = (a.g.lq + TM - 1) / TM;
-    bwd_dq_bf16_kernel<<<(unsigned)(a.g.nq * n_q_tiles), 256, 0, s>>>(a, n_q_tiles);
+    const int n_q_tiles = (a.g.lq + WG_ROWS - 1) / WG_ROWS;
+    bwd_dq_bf16_kernel<<<(unsigned)(a.g.nq * n_q_tiles), 512, 0, s>>>(a, n_q_tiles);
     return hipGetLastError();
 }

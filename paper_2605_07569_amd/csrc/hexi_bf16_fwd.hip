@@ -28,8 +28,6 @@
 // the exact one defines the LSE, the one of the bf16-rounded probabilities normalises O.
 #include "hexi_internal.h"
 #include "hexi_mfma.h"
-#include <type_traits>
-#include <utility>
 
 namespace {
 
@@ -66,35 +64,6 @@ struct FwdSmem {
     // the epilogue stages 8 x (32 x 132 + 32) floats over the start of this struct
 };
 static_assert(sizeof(FwdSmem) >= 8 * (32 * O_STAGE_STRIDE + 32) * 4, "epilogue staging does not fit");
-
-template <int N> using IC = std::integral_constant<int, N>;
-
-// f(IC<FIRST>{}), ..., f(IC<LAST - 1>{})
-template <int FIRST, int... I, class F> __device__ __forceinline__ void for_range_impl(std::integer_sequence<int, I...>, F& f)
-{
-    (f(IC<FIRST + I>{}), ...);
-}
-template <int FIRST, int LAST, class F> __device__ __forceinline__ void for_range(F& f)
-{
-    for_range_impl<FIRST>(std::make_integer_sequence<int, LAST - FIRST>{}, f);
-}
-
-__device__ __forceinline__ void wait_vm(int allowed_tiles)
-{
-    // each wavefront issues DMA_PER_WAVE global->LDS loads per tile; they complete in order
-    static_assert(DMA_PER_WAVE == 5, "wait counts below assume 5 transfers per tile");
-    if (allowed_tiles >= 3) asm volatile("s_waitcnt vmcnt(15)" ::: "memory");
-    else if (allowed_tiles == 2) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
-    else if (allowed_tiles == 1) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-}
-
-__device__ __forceinline__ void wg_barrier()
-{
-    __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-}
 
 __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const int n_q_tiles)
 {
@@ -177,14 +146,20 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
         const int col0 = tile * TN;
         const uint32_t dst = __builtin_amdgcn_readfirstlane(fetch_lds + (tile & (NB - 1)) * fetch_tile_bytes + wg * 1024);
         const uint16_t* src = fetch_src + (long long)col0 * g.kv_stride_tok;
-        const bool ragged = col0 + TN > g.lc;   // last tile: clamp the key index (the extra keys are masked through their position)
+        if (col0 + TN <= g.lc) {
 #pragma unroll
-        for (int i = 0; i < DMA_PER_WAVE; ++i) {
-            uint32_t off = fetch_off[i];
-            if (ragged && col0 + fetch_row[i] >= g.lc)
-                off -= 2u * (uint32_t)((col0 + fetch_row[i] - (g.lc - 1)) * (int)g.kv_stride_tok);
-            const uint32_t d = wg + 4 * i < n_xfer ? dst + i * 4096 : lds_dump;
-            lds_dma16_base(src, off, __builtin_amdgcn_readfirstlane(d));
+            for (int i = 0; i < DMA_PER_WAVE; ++i) {
+                const uint32_t d = wg + 4 * i < n_xfer ? dst + i * 4096 : lds_dump;
+                lds_dma16_base(src, fetch_off[i], __builtin_amdgcn_readfirstlane(d));
+            }
+        } else {   // ragged last tile: clamp the key index (the extra keys are masked through their position)
+#pragma unroll
+            for (int i = 0; i < DMA_PER_WAVE; ++i) {
+                uint32_t off = fetch_off[i];
+                if (col0 + fetch_row[i] >= g.lc) off -= 2u * (uint32_t)((col0 + fetch_row[i] - (g.lc - 1)) * (int)g.kv_stride_tok);
+                const uint32_t d = wg + 4 * i < n_xfer ? dst + i * 4096 : lds_dump;
+                lds_dma16_base(src, off, __builtin_amdgcn_readfirstlane(d));
+            }
         }
         // global positions of the tile's keys, for the tiles some row needs a mask for
         if (grp == 1 && wg == 0 && tile >= n_full_wg) {
@@ -344,18 +319,18 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
             for (int j = 0; j < n_pre && j < NT; ++j) fetch_tile(j);
         }
         if (grp == 1) {   // K(0) complete before anyone's M(0)
-            wait_vm((NT < K_AHEAD ? NT : K_AHEAD) - 1);
+            wait_tiles_in_flight((NT < K_AHEAD ? NT : K_AHEAD) - 1);
             wg_barrier();
         }
         // before M(t): group 0 has requested V up to min(t + 1, NT - 1) and needs V(t - 1) complete
         auto enter_m = [&](int t) __attribute__((always_inline)) {
-            if (grp == 0) wait_vm(NT - t < 2 ? NT - t : 2);
+            if (grp == 0) wait_tiles_in_flight(NT - t < 2 ? NT - t : 2);
             wg_barrier();
         };
         // before V(t): group 1 has requested K up to min(t + 3, NT - 1) and needs K(t + 1) complete; then the
         // vector phase itself, starting with this group's share of the fetches
         auto vector_part = [&](int t, auto first_c) __attribute__((always_inline)) {
-            if (grp == 1 && t + 1 < NT) wait_vm(NT - 2 - t < 2 ? NT - 2 - t : 2);
+            if (grp == 1 && t + 1 < NT) wait_tiles_in_flight(NT - 2 - t < 2 ? NT - 2 - t : 2);
             wg_barrier();
             const int j = t + (grp ? K_AHEAD : V_AHEAD);
             if (j < NT) fetch_tile(j);

@@ -11,6 +11,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
+#include <utility>
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -174,3 +176,45 @@ __device__ __forceinline__ void pin(const bf16x8& x) { asm volatile("" ::"v"(x))
 #define HEXI_SCHED_DSREAD(n) __builtin_amdgcn_sched_group_barrier(0x100, n, 0)
 #define HEXI_SCHED_DSWRITE(n) __builtin_amdgcn_sched_group_barrier(0x200, n, 0)
 #define HEXI_SCHED_VALU(n) __builtin_amdgcn_sched_group_barrier(0x002, n, 0)
+
+// ---- helpers of the ping-pong kernels (8 wavefronts, two groups alternating matrix and vector phases) ----
+
+template <int N> using IC = std::integral_constant<int, N>;
+
+// f(IC<FIRST>{}), ..., f(IC<LAST - 1>{})
+template <int FIRST, int... I, class F> __device__ __forceinline__ void for_range_impl(std::integer_sequence<int, I...>, F& f)
+{
+    (f(IC<FIRST + I>{}), ...);
+}
+template <int FIRST, int LAST, class F> __device__ __forceinline__ void for_range(F& f)
+{
+    for_range_impl<FIRST>(std::make_integer_sequence<int, LAST - FIRST>{}, f);
+}
+
+// Tiles are fetched with 5 wave-wide global->LDS transfers per wavefront per tile; transfers complete in
+// order, so "at most `allowed_tiles` younger tiles still in flight" is a vmcnt of 5 per tile.
+__device__ __forceinline__ void wait_tiles_in_flight(int allowed_tiles)
+{
+    if (allowed_tiles >= 3) asm volatile("s_waitcnt vmcnt(15)" ::: "memory");
+    else if (allowed_tiles == 2) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+    else if (allowed_tiles == 1) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+// Workgroup barrier that the compiler's scheduler does not move code across.
+__device__ __forceinline__ void wg_barrier()
+{
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// LDS tile layout of the kernels that read a [64 rows][128 bf16] tile both row-wise (128-bit reads, 32
+// consecutive rows across the lanes) and transposed (ds_read_b64_tr_b16, 4 consecutive rows per 16-lane
+// group): rows are 272 bytes apart (256 + 16 of padding) and stored in the order p16_row(), which swaps
+// the two 2-bit digits of the row index inside every block of 16 rows.  Consecutive rows r..r+3 then sit 4
+// LDS rows (= 16 banks) apart, so both access patterns touch all 64 banks exactly once, and every operand
+// fragment is at (one per-lane base register) + (a compile-time offset).
+constexpr int P16_ROW_BYTES = 272;
+constexpr int P16_TILE_BYTES = 64 * P16_ROW_BYTES;   // 17 KB = 17 wave-wide 1 KB transfers
+__host__ __device__ constexpr int p16_row(int r) { return (r & ~15) | ((r & 3) << 2) | ((r >> 2) & 3); }
