@@ -1,72 +1,85 @@
-// bf16 backward ring step, dK / dV part, for gfx950: one workgroup (4 wavefronts, one per SIMD) per
-// (128-key tile, q head).
+// bf16 backward ring step, dK / dV part, for gfx950: one workgroup of 8 wavefronts per (128-key tile, q head),
+// one workgroup per CU.
 //
-// The workgroup keeps its K and V rows in registers as MFMA operands and its dK / dV tiles in
-// accumulators while it sweeps the 64-row q tiles that can see the key tile.  Per q tile:
-// S = Q K^T and dP = dO V^T (keys across lanes, query rows in-lane), P = exp2(S*scale*log2e -
-// LSE*log2e) from the saved global LSE, dS = P (dP - Delta); the accumulator registers holding P
-// and dS are already in operand order for dV += P^T dO and dK += dS^T Q (dO and Q fetched with
-// transposed LDS reads).  dQ is produced by a separate q-stationary kernel: adding it from here
-// would need one fp32 atomic per dS K element per key tile, and that atomic traffic (about
-// 3 bytes per kFLOP at 128 keys per workgroup) saturates the L2 atomic units long before the MFMA
-// pipes; recomputing S and dP in the dQ kernel costs 2 extra matmuls out of 5 but keeps every
-// product on the matrix cores.
+// The workgroup keeps its K and V rows in registers as MFMA operands and its dK / dV tiles in accumulators
+// while it sweeps the 64-row q tiles that can see the key tile.  Per q tile: S = Q K^T and dP = dO V^T (keys
+// across lanes, query rows in-lane), P = exp2(S*scale*log2e - LSE*log2e) from the saved global LSE,
+// dS = P (dP - Delta), dV += P^T dO and dK += dS^T Q (dO and Q fetched with transposed LDS reads).  dQ is
+// produced by a separate q-stationary kernel: adding it from here would need one fp32 atomic per dS K element
+// per key tile, and that atomic traffic saturates the L2 atomic units long before the MFMA pipes.
 //
-// Pipeline: Q / dO tiles are double-buffered in LDS and fetched one tile ahead with direct
-// global->LDS loads, one barrier per tile.  LDS tiles are XOR-swizzled (no padding) so that both the
-// 128-bit row reads and the transposed 64-bit reads are bank-conflict free.
+// Ping-pong schedule (see the forward kernel): two groups of four wavefronts, wavefront w and w + 4 on one
+// SIMD, alternate between a matrix phase and a vector phase with one workgroup barrier per phase, group 1 one
+// phase behind group 0, so that every SIMD always has one wavefront issuing only MFMAs (and their LDS reads)
+// and one issuing only VALU work.  Two wavefronts per SIMD leave 256 registers per wavefront, too few for
+// 32 keys x 128 columns of dK and dV (128 registers) next to the K / V fragments (64): the wavefronts of a
+// group therefore work in pairs on 32 keys.  Each of the two computes S, dP, P, dS for one 32-row half of
+// the q tile, publishes its P^T / dS^T operand fragments (bf16, 4 KB) in LDS, and accumulates dV and dK over
+// all 64 rows for one 64-column half of the head dimension: no product is computed twice, and the
+// accumulators shrink to 64 registers.
+//   M(i): dV += P^T dO, dK += dS^T Q of tile i-1 (16 MFMAs), then S and dP of tile i (16 MFMAs);
+//   V(i): P and dS of tile i, rounded to bf16 operand slots and written to the exchange area.
+// Q / dO tiles are triple-buffered in LDS (padded, row-permuted layout: conflict-free row and transposed reads
+// from single base registers) and fetched two tiles ahead with direct global->LDS loads: Q by group 1 at the
+// start of its vector phase, dO (+ LSE, Delta) by group 0 at the start of the matrix phase it runs in the
+// same slot.
 //
-// The q heads of a GQA group run in different workgroups and add their dK / dV tiles with fp32
-// atomics (plain stores when the group has a single head), so dk/dv must be zero-filled (or hold
-// the running sum under HEXI_ACCUMULATE) before the launch.
+// The q heads of a GQA group run in different workgroups and add their dK / dV tiles with fp32 atomics (plain
+// stores when the group has a single head), so dk/dv must be zero-filled (or hold the running sum under
+// HEXI_ACCUMULATE) before the launch.
 #include "hexi_internal.h"
 #include "hexi_mfma.h"
-#include <type_traits>
 
 namespace {
 
 constexpr int D = 128;
-constexpr int TN = 128;          // keys per workgroup (32 per wavefront)
-constexpr int TM = 64;           // q rows per inner tile
+constexpr int WG_KEYS = 128;     // keys per workgroup: 2 groups x 2 pairs x 32
+constexpr int TM = 64;           // q rows per tile
+constexpr int NB = 3;            // LDS buffers per tensor
+constexpr int DMA_PER_WAVE = 5;  // tile transfers per wavefront per tile (17 real ones per tile, 3 dummies)
 constexpr float LOG2E = 1.4426950408889634f;
 
-// [rows][128] bf16 tile, 16-byte chunk c of row r stored at chunk position c ^ swz_row(r)
-__device__ __forceinline__ int swz_row(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
-
 struct BwdSmem {
-    uint16_t q[2][TM * D];        // 2 x 16 KB
-    uint16_t g[2][TM * D];        // dO, 2 x 16 KB
-    float lse[2][TM];
-    float delta[2][TM];
-    int qpos[2][TM];
+    unsigned char q[NB][P16_TILE_BYTES];   // 3 x 17 KB
+    unsigned char g[NB][P16_TILE_BYTES];   // dO, 3 x 17 KB
+    unsigned char xch[8][4096];            // per wavefront: P^T fragments 0, 1 and dS^T fragments 0, 1 (64 lanes x 16 B each)
+    float lse[NB][TM];
+    float delta[NB][TM];
+    int qpos[8][TM];                       // row positions of the tiles that need a mask, written two tiles ahead
+    unsigned char dump[1024];              // destination of the dummy transfers
 };
 
+// LDS reads of matrix-phase step st: two transposed reads (+ one P^T / dS^T fragment on even steps) below 16,
+// one row read from 16 on
+__host__ __device__ constexpr int reads_of(int st) { return st < 16 ? 2 + ((st & 1) == 0 ? 1 : 0) : 1; }
+
 template <bool ATOMIC_DKV>
-__global__ void __launch_bounds__(256) bwd_dkdv_bf16_kernel(const BwdArgs a, const int n_kv_tiles)
+__global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, const int n_kv_tiles)
 {
     const AttnGeom& g = a.g;
     __shared__ __attribute__((aligned(1024))) BwdSmem sm;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = wave >> 2, wg4 = wave & 3, pair = wg4 >> 1, hd = wg4 & 1;
     const int l32 = lane & 31, hh = lane >> 5;
     const int grp2 = (lane >> 4) & 1, j16 = lane & 15;
 
-    // Work mapping: consecutive workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a
-    // contiguous range of (head, key tile) units so that the workgroups sharing an L2 stream the
-    // same head's Q / dO tiles.
+    // Work mapping: consecutive workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a contiguous
+    // range of (head, key tile) units so that the workgroups sharing an L2 stream the same head's Q / dO tiles.
     const int n_units = g.nq * n_kv_tiles;
-    int unit = blockIdx.x;
+    int unit;
     {
         const int per = n_units / 8, rem = n_units % 8;
         const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-        // XCD x owns per + (x < rem) units starting at x*per + min(x, rem)
         unit = xcd * per + (xcd < rem ? xcd : rem) + slot;
     }
     const int h = unit / n_kv_tiles;
     const int kv_tile = unit - h * n_kv_tiles;
     const int kvh = g.kv_of_q[h];
-    const int col0 = kv_tile * TN;
-    const int my_col = col0 + 32 * wave + l32;
+    const int col0 = kv_tile * WG_KEYS;
+    const int wcol0 = col0 + 64 * grp + 32 * pair;     // first key of this wavefront pair
+    const int my_col = wcol0 + l32;
     const int my_col_c = my_col < g.lc ? my_col : g.lc - 1;
     const int my_kpos = my_col < g.lc ? seg_pos_of_row(g.ks, my_col) : 0x7fffffff;
 
@@ -77,12 +90,12 @@ __global__ void __launch_bounds__(256) bwd_dkdv_bf16_kernel(const BwdArgs a, con
     const float* lse_h = a.lse + (long long)h * g.lq;
     const float* delta_h = a.delta + (long long)h * g.lq;
 
-    // q rows that see at least one key of the tile form a suffix of the shard; rows that see all of
+    // q rows that see at least one key of the workgroup's tile form a suffix of the shard; rows that see all of
     // its keys form a (shorter) suffix
-    const int last_col = (col0 + TN < g.lc ? col0 + TN : g.lc) - 1;
+    const int last_col = (col0 + WG_KEYS < g.lc ? col0 + WG_KEYS : g.lc) - 1;
     const int k_min = seg_pos_of_row(g.ks, col0), k_max = seg_pos_of_row(g.ks, last_col);
     const int qt_begin = seg_rows_le(g.qs, k_min - 1) / TM;
-    const int qt_full = (col0 + TN <= g.lc) ? (seg_rows_le(g.qs, k_max - 1) + TM - 1) / TM : 0x7fffffff;
+    const int qt_full = (col0 + WG_KEYS <= g.lc) ? (seg_rows_le(g.qs, k_max - 1) + TM - 1) / TM : 0x7fffffff;
     const int n_qtiles = (g.lq + TM - 1) / TM;
 
     // K^T and V^T operand fragments of S = Q K^T and dP = dO V^T: lane (key l32, half hh) holds
@@ -98,219 +111,240 @@ __global__ void __launch_bounds__(256) bwd_dkdv_bf16_kernel(const BwdArgs a, con
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) { pin(kf[ks]); pin(vf[ks]); }
     }
-    f32x16 dk_acc[4], dv_acc[4];
+    // dK / dV of this wavefront: 32 keys x columns [64*hd, 64*hd + 64), two 32-column blocks
+    f32x16 dk_acc[2], dv_acc[2];
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+    for (int db = 0; db < 2; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) { dk_acc[db][r] = 0.f; dv_acc[db][r] = 0.f; }
     const float scale_log2 = g.scale * LOG2E;
 
-    // Direct global->LDS fetch of one q tile (Q and dO, 16 KB each): 16 wave-instructions of 1 KB per
-    // tensor, 4 per wavefront; lane L of instruction i fills chunk position L%16 of row 4*i + L/16.
-    // The loads are issued through inline assembly so that the compiler does not serialise later
-    // LDS reads of the OTHER buffer behind them; they are waited for explicitly (vmcnt(0)) right
-    // before the barrier that publishes the tile.
-    int fetch_off[4];
+    // Tile order: first the tiles that need masking (the leading, partly visible q tiles and a ragged last
+    // tile), then the fully visible ones.
+    const int n_all = n_qtiles - qt_begin;
+    const bool ragged = n_qtiles * TM > g.lq;
+    const int lead = n_all > 0 ? (qt_full < n_qtiles ? qt_full : n_qtiles) - qt_begin : 0;     // partly visible tiles
+    const bool extra = ragged && qt_begin + lead < n_qtiles;                                    // ragged last tile not among them
+    const int n_masked = lead + (extra ? 1 : 0);
+    auto tile_of = [&](int i) { return i < lead ? qt_begin + i : (i < n_masked ? n_qtiles - 1 : qt_begin + lead + (i - n_masked)); };
+
+    // Direct global->LDS fetch of one 64-row tile by the four wavefronts of a group (group 1: Q, group 0: dO).
+    // A transfer is one wave-wide instruction: lane L writes the 16 bytes at (transfer * 1024 + 16 * L) of the
+    // tile's LDS image and reads the 16-byte piece of the q row that belongs there (the pad piece re-reads
+    // piece 0).  Wavefront wg4 issues transfers wg4, wg4 + 4, ..., wg4 + 16; transfer numbers past the tile's
+    // end go to a dump area.
+    constexpr int N_XFER = P16_TILE_BYTES / 1024;
+    uint32_t fetch_off[DMA_PER_WAVE];   // byte offsets from the tile's first row
+    int fetch_row[DMA_PER_WAVE];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int r = (wave * 4 + i) * 4 + (lane >> 4);
-        fetch_off[i] = r * (int)g.q_stride_tok + (((lane & 15) ^ swz_row(r)) << 3);
+    for (int i = 0; i < DMA_PER_WAVE; ++i) {
+        const int pos = (wg4 + 4 * i) * 1024 + 16 * lane;
+        int r = pos / P16_ROW_BYTES, c = (pos - r * P16_ROW_BYTES) >> 4;
+        r = p16_row(r);     // the permutation is its own inverse: LDS row -> q row
+        if (wg4 + 4 * i >= N_XFER) r = 0;
+        if (c >= 16) c = 0;
+        fetch_row[i] = r;
+        fetch_off[i] = 2u * (uint32_t)(r * (int)g.q_stride_tok + c * 8);
     }
     const uint32_t lds_q = (uint32_t)(uintptr_t)(&sm.q[0][0]), lds_g = (uint32_t)(uintptr_t)(&sm.g[0][0]);
+    const uint32_t lds_dump = (uint32_t)(uintptr_t)(&sm.dump[0]);
     const uint32_t lds_lse = (uint32_t)(uintptr_t)(&sm.lse[0][0]), lds_delta = (uint32_t)(uintptr_t)(&sm.delta[0][0]);
-    auto fetch_tile = [&](int qt, int buf) {
+    const uint16_t* fetch_src = grp ? q : go;
+    const uint32_t fetch_lds = grp ? lds_q : lds_g;
+    auto fetch_tile = [&](int i) {     // i: index in processing order; buffer i % NB
+        const int qt = tile_of(i);
         const int row0 = qt * TM;
-        const uint32_t wq = __builtin_amdgcn_readfirstlane(lds_q + buf * (TM * D * 2) + wave * 4096);
-        const uint32_t wg = __builtin_amdgcn_readfirstlane(lds_g + buf * (TM * D * 2) + wave * 4096);
+        const int buf = i % NB;
+        const uint32_t dst = __builtin_amdgcn_readfirstlane(fetch_lds + buf * P16_TILE_BYTES + wg4 * 1024);
+        const uint16_t* src = fetch_src + (long long)row0 * g.q_stride_tok;
         if (row0 + TM <= g.lq) {
-            const uint16_t* qb = q + (long long)row0 * g.q_stride_tok;
-            const uint16_t* gb = go + (long long)row0 * g.q_stride_tok;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                lds_dma16(qb + fetch_off[i], wq + i * 1024);
-                lds_dma16(gb + fetch_off[i], wg + i * 1024);
+            for (int t = 0; t < DMA_PER_WAVE; ++t) {
+                const uint32_t d = wg4 + 4 * t < N_XFER ? dst + t * 4096 : lds_dump;
+                lds_dma16_base(src, fetch_off[t], __builtin_amdgcn_readfirstlane(d));
             }
         } else {   // ragged last tile: clamp the row index (the extra rows are masked out through their position)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int r = (wave * 4 + i) * 4 + (lane >> 4);
-                const int c = (lane & 15) ^ swz_row(r);
-                const int row = row0 + r < g.lq ? row0 + r : g.lq - 1;
-                const long long off = (long long)row * g.q_stride_tok + c * 8;
-                lds_dma16(q + off, wq + i * 1024);
-                lds_dma16(go + off, wg + i * 1024);
+            for (int t = 0; t < DMA_PER_WAVE; ++t) {
+                uint32_t off = fetch_off[t];
+                if (row0 + fetch_row[t] >= g.lq) off -= 2u * (uint32_t)((row0 + fetch_row[t] - (g.lq - 1)) * (int)g.q_stride_tok);
+                const uint32_t d = wg4 + 4 * t < N_XFER ? dst + t * 4096 : lds_dump;
+                lds_dma16_base(src, off, __builtin_amdgcn_readfirstlane(d));
             }
         }
-        // per-row scalars: one 4-byte-per-lane instruction each (LSE by wavefront 0, Delta by wavefront 1)
-        if (wave < 2) {
-            const int row = row0 + lane < g.lq ? row0 + lane : g.lq - 1;
-            const float* src = (wave == 0 ? lse_h : delta_h) + row;
-            lds_dma4(src, __builtin_amdgcn_readfirstlane((wave == 0 ? lds_lse : lds_delta) + buf * (TM * 4)));
+        if (grp == 0) {
+            // per-row scalars: one 4-byte-per-lane transfer each (LSE by wavefront 0, Delta by wavefront 1)
+            if (wg4 < 2) {
+                const int row = row0 + lane < g.lq ? row0 + lane : g.lq - 1;
+                const float* src4 = (wg4 == 0 ? lse_h : delta_h) + row;
+                lds_dma4(src4, __builtin_amdgcn_readfirstlane((wg4 == 0 ? lds_lse : lds_delta) + buf * (TM * 4)));
+            }
+        } else if (wg4 == 0 && i < n_masked) {
+            // global positions of the tile's rows, only for tiles that need masking
+            sm.qpos[i & 7][lane] = row0 + lane < g.lq ? seg_pos_of_row(g.qs, row0 + lane) : -1;
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         }
-        // global positions of the tile's rows, only for tiles that need masking
-        if (wave == 2 && (qt < qt_full || row0 + TM > g.lq))
-            sm.qpos[buf][lane] = row0 + lane < g.lq ? seg_pos_of_row(g.qs, row0 + lane) : -1;
     };
 
-    const int sw_l32 = swz_row(l32);
-    const int jj = j16 >> 2, cl = 2 * grp2 + ((j16 & 3) >> 1);
+    // Lane parts of the LDS byte addresses; buffer and step are compile-time offsets of the reads.
+    //   row fragment ks of the wavefront's 32-row half, buffer B:   nat_addr[which] + B * TILE + 32 * ks
+    //   transposed fragment (16-row step kq, 32-column block db, half `second`) of buffer B: rows
+    //   16kq + 8*second + 4*hh + jj sit in LDS rows 16kq + 4*jj + 2*second + hh:
+    //        tr_addr[which] + B * TILE + (16 * kq + 2 * second) * ROW + 64 * db     (columns 64*hd + 32*db + ...)
+    //   P^T / dS^T fragment f of the pair's wavefront w':  xch_addr + w' * 4096 + f * 1024
+    // which = 0: dO tile, 1: Q tile for the transposed reads; 0: Q tile, 1: dO tile for the row reads.
+    const int jj = j16 >> 2;
+    const uint32_t nat_lane = (32 * hd + p16_row(l32)) * P16_ROW_BYTES + 16 * hh;
+    const uint32_t tr_lane = (4 * jj + hh) * P16_ROW_BYTES + 2 * (16 * grp2 + 4 * (j16 & 3)) + 128 * hd;
+    uint32_t nat_addr[2] = {lds_q + nat_lane, lds_g + nat_lane};
+    uint32_t tr_addr[2] = {lds_g + tr_lane, lds_q + tr_lane};
+    const uint32_t lds_xch = (uint32_t)(uintptr_t)(&sm.xch[0][0]);
+    const uint32_t xch_addr = lds_xch + (wave & ~1) * 4096 + lane * 16;
+    bf16x8* xch_mine = reinterpret_cast<bf16x8*>(&sm.xch[wave][0]) + lane;
 
-    // One q tile.  The two 32-row q blocks are staggered so that the VALU work of one block sits
-    // between MFMAs of the other in program order (the matrix pipe keeps running under the VALU):
-    //   A: S/dP(block 0) | B: S/dP(block 1) + VALU(block 0) | C: dV/dK(block 0) + VALU(block 1) | D: dV/dK(block 1)
-    // Each step (2 MFMAs, their LDS prefetches, 2 elements of VALU work) ends in a scheduling barrier,
-    // so the hand-written interleave is what gets issued.  MASKED is a compile-time flag: masked tiles
-    // take a copy of the body with selects, unmasked ones carry no per-element masking at all.
-    // Lane parts of the LDS addresses (elements): everything else (q block, step, buffer) is a compile-time
-    // offset, so the reads need no address arithmetic inside the loop.
-    int nat_lane[8], tr_lane[8];
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) nat_lane[ks] = l32 * D + (((2 * ks + hh) ^ sw_l32) << 3);
-#pragma unroll
-    for (int x = 0; x < 8; ++x) {   // x = 2*db + second
-        const int db = x >> 1, second = x & 1;
-        tr_lane[x] = (4 * hh + jj + 8 * second) * D + ((((db ^ jj) << 2) | (cl ^ (hh + 2 * second))) << 3) + 4 * (j16 & 1);
-    }
-    auto tile_body = [&](auto buf_c, auto masked_c) __attribute__((always_inline)) {
+    f32x16 s, dp;
+
+    // Matrix phase on buffers (B + NB - 1) % NB (previous tile) and B (this tile).  Steps 0..15: dV += P^T dO
+    // and dK += dS^T Q of the previous tile: 16-row step kq = st / 4 (rows 0..31 are wavefront hd = 0's, 32..63
+    // wavefront hd = 1's), product (st / 2) % 2, column block st % 2.  Steps 16..31: S and dP of this tile's
+    // 32-row half, alternating, ks = (st - 16) / 2.  [FIRST, LAST) selects the steps; operand fragments are
+    // requested PF steps ahead.
+    auto m_phase = [&](auto bc, auto first_c, auto last_c) __attribute__((always_inline)) {
+        constexpr int B = decltype(bc)::value, FIRST = decltype(first_c)::value, LAST = decltype(last_c)::value;
+        constexpr int PF = 3, NS = PF + 1;   // a fragment's registers are busy from its request until its MFMA
+        constexpr int BP = (B + NB - 1) % NB;
+        s16x4 ta[NS], tb[NS];
+        bf16x8 nb[NS];
+        bf16x8 af[3];                        // P^T / dS^T fragments: shared by the two column blocks of a step pair
+        auto issue = [&](auto stc) __attribute__((always_inline)) {
+            constexpr int st = decltype(stc)::value, slot = (st - FIRST) % NS;
+            if constexpr (st < 16) {
+                constexpr int db = st & 1, which = (st >> 1) & 1, kq = st >> 2;
+                if constexpr (db == 0)
+                    lds_issue_b128<(kq >> 1) * 4096 + (2 * which + (kq & 1)) * 1024>(af[(st >> 1) % 3], xch_addr);
+                constexpr int off = BP * P16_TILE_BYTES + 16 * kq * P16_ROW_BYTES + 64 * db;
+                lds_issue_tr16<off>(ta[slot], tr_addr[which]);
+                lds_issue_tr16<off + 2 * P16_ROW_BYTES>(tb[slot], tr_addr[which]);
+            } else {
+                constexpr int which = (st - 16) & 1, ks = (st - 16) >> 1;
+                lds_issue_b128<B * P16_TILE_BYTES + 32 * ks>(nb[slot], nat_addr[which]);
+            }
+        };
+        auto step = [&](auto stc) __attribute__((always_inline)) {
+            constexpr int st = decltype(stc)::value, slot = (st - FIRST) % NS;
+            if constexpr (st + PF < LAST) issue(IC<st + PF>{});
+            // LDS reads younger than this step's fragments: those of the next PF steps that exist
+            constexpr int hi = st + PF < LAST ? st + PF : LAST - 1;
+            constexpr int younger = (hi >= st + 1 ? reads_of(st + 1) : 0) + (hi >= st + 2 ? reads_of(st + 2) : 0) +
+                                    (hi >= st + 3 ? reads_of(st + 3) : 0);
+            static_assert(PF == 3, "the sum above covers three steps");
+            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            if constexpr (st < 16) {
+                constexpr int db = st & 1, which = (st >> 1) & 1;
+                // the wait ties all three registers: the P^T / dS^T fragment was requested before the transposed pair
+                asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(ta[slot]), "+v"(tb[slot]), "+v"(af[(st >> 1) % 3]) : "n"(younger));
+                const bf16x8 bfrag = join_halves(ta[slot], tb[slot]);
+                if constexpr (which == 0) dv_acc[db] = mfma32(af[(st >> 1) % 3], bfrag, dv_acc[db]);
+                else dk_acc[db] = mfma32(af[(st >> 1) % 3], bfrag, dk_acc[db]);
+            } else {
+                constexpr int which = (st - 16) & 1, ks = (st - 16) >> 1;
+                lds_wait<younger>(nb[slot]);
+                if constexpr (which == 0) s = mfma32(nb[slot], kf[ks], ks == 0 ? zero : s);
+                else dp = mfma32(nb[slot], vf[ks], ks == 0 ? zero : dp);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        __builtin_amdgcn_sched_barrier(0);
+        for_range<FIRST, (FIRST + PF < LAST ? FIRST + PF : LAST)>(issue);
+        for_range<FIRST, LAST>(step);
+    };
+
+    // Vector phase: P and dS of the wavefront's 32 rows x 32 keys.  Register x = 4*rb + t holds row
+    // 32*hd + 8*rb + 4*hh + t.  Rows whose LSE is -inf see nothing anywhere, so they only occur in masked tiles.
+    auto v_phase = [&](int buf, int qpos_slot, auto masked_c) __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked_c)::value;
-        constexpr int buf = decltype(buf_c)::value;
-        const uint16_t* Qs = &sm.q[buf][0];
-        const uint16_t* Gs = &sm.g[buf][0];
-        f32x16 s[2], dp[2];
-        bf16x8 pf[4], df[4];
-        f32x4 lse4[2][4], del4[2][4];     // per-row constants of the rows this lane holds: i = 32*b + 8*rb + 4*hh + t
-        constexpr int PF = 3;             // LDS fragments requested this many steps ahead of their MFMA
-        bf16x8 ra[PF], rb_[PF];
-
-        auto nat_off = [&](int b, int ks) { return nat_lane[ks] + 32 * b * D; };
-        auto tr_off = [&](int b, int st, int second) { return tr_lane[2 * (st & 3) + second] + 16 * (2 * b + (st >> 2)) * D; };
-        auto load_nat = [&](int b, int ks, int slot) {
-            ra[slot] = *reinterpret_cast<const bf16x8*>(&Qs[nat_off(b, ks)]);
-            rb_[slot] = *reinterpret_cast<const bf16x8*>(&Gs[nat_off(b, ks)]);
-        };
-        auto load_tr = [&](int b, int st, int slot) {
-            ra[slot] = lds_tr_pair(&Gs[tr_off(b, st, 0)], &Gs[tr_off(b, st, 1)]);
-            rb_[slot] = lds_tr_pair(&Qs[tr_off(b, st, 0)], &Qs[tr_off(b, st, 1)]);
-        };
-        // P and dS of elements e, e+1 of q block b.  Rows whose LSE is -inf see nothing anywhere, so they
-        // are masked in every tile they appear in.
-        auto valu2 = [&](int b, int e) {
+        float p[16], ds[16];
 #pragma unroll
-            for (int x = e; x < e + 2; ++x) {
-                const int rb = x >> 2, t = x & 3;
-                float p = fast_exp2(fmaf(s[b][x], scale_log2, lse4[b][rb][t]));
-                if (MASKED) p = (my_kpos > sm.qpos[buf][32 * b + 8 * rb + 4 * hh + t]) ? 0.f : p;
-                s[b][x] = p;
-                dp[b][x] = p * (dp[b][x] - del4[b][rb][t]);
+        for (int rb = 0; rb < 4; ++rb) {
+            const int r0 = 32 * hd + 8 * rb + 4 * hh;
+            const f32x4 l4 = *reinterpret_cast<const f32x4*>(&sm.lse[buf][r0]);
+            const f32x4 d4 = *reinterpret_cast<const f32x4*>(&sm.delta[buf][r0]);
+            int4 qp = make_int4(0, 0, 0, 0);
+            if (MASKED) qp = *reinterpret_cast<const int4*>(&sm.qpos[qpos_slot][r0]);
+            const int qpv[4] = {qp.x, qp.y, qp.z, qp.w};
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int x = 4 * rb + t;
+                float pv = fast_exp2(fmaf(s[x], scale_log2, -LOG2E * l4[t]));
+                if (MASKED) pv = my_kpos > qpv[t] ? 0.f : pv;
+                p[x] = pv;
+                ds[x] = pv * (dp[x] - d4[t]);
             }
-        };
-        auto pack = [&](int b, int half) {
-            const int x = 8 * half;
-            pf[2 * b + half] = pack_bf16x8(s[b][x], s[b][x + 1], s[b][x + 2], s[b][x + 3], s[b][x + 4], s[b][x + 5], s[b][x + 6], s[b][x + 7]);
-            df[2 * b + half] = pack_bf16x8(dp[b][x], dp[b][x + 1], dp[b][x + 2], dp[b][x + 3], dp[b][x + 4], dp[b][x + 5], dp[b][x + 6], dp[b][x + 7]);
-        };
-
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) { s[b][r] = 0.f; dp[b][r] = 0.f; }
-        // phase A: S/dP of block 0; the row constants are fetched alongside
-#pragma unroll
-        for (int ks = 0; ks < PF; ++ks) load_nat(0, ks, ks);
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 qa = ra[ks % PF], ga = rb_[ks % PF];      // ring slot = (global step) % PF
-            if (ks + PF < 8) load_nat(0, ks + PF, ks % PF);
-            else load_nat(1, ks + PF - 8, ks % PF);
-            {
-                const int b = ks >> 2, rb = ks & 3;
-                const f32x4 l = *reinterpret_cast<const f32x4*>(&sm.lse[buf][32 * b + 8 * rb + 4 * hh]);
-                lse4[b][rb] = f32x4{-LOG2E * l[0], -LOG2E * l[1], -LOG2E * l[2], -LOG2E * l[3]};
-                del4[b][rb] = *reinterpret_cast<const f32x4*>(&sm.delta[buf][32 * b + 8 * rb + 4 * hh]);
-            }
-            s[0] = mfma32(qa, kf[ks], s[0]);
-            dp[0] = mfma32(ga, vf[ks], dp[0]);
-            __builtin_amdgcn_sched_barrier(0);
         }
-        // phase B: S/dP of block 1, VALU of block 0
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 qa = ra[(8 + ks) % PF], ga = rb_[(8 + ks) % PF];
-            if (ks + PF < 8) load_nat(1, ks + PF, (8 + ks) % PF);
-            else load_tr(0, ks + PF - 8, (8 + ks) % PF);
-            s[1] = mfma32(qa, kf[ks], s[1]);
-            dp[1] = mfma32(ga, vf[ks], dp[1]);
-            valu2(0, 2 * ks);
-            if (ks == 4) pack(0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        pack(0, 1);
-        // phase C: dV/dK of block 0, VALU of block 1
-#pragma unroll
-        for (int st = 0; st < 8; ++st) {
-            const bf16x8 gf = ra[(16 + st) % PF], qf = rb_[(16 + st) % PF];
-            if (st + PF < 8) load_tr(0, st + PF, (16 + st) % PF);
-            else load_tr(1, st + PF - 8, (16 + st) % PF);
-            dv_acc[st & 3] = mfma32(pf[st >> 2], gf, dv_acc[st & 3]);
-            dk_acc[st & 3] = mfma32(df[st >> 2], qf, dk_acc[st & 3]);
-            valu2(1, 2 * st);
-            if (st == 4) pack(1, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        pack(1, 1);
-        // phase D: dV/dK of block 1
-#pragma unroll
-        for (int st = 0; st < 8; ++st) {
-            const bf16x8 gf = ra[(24 + st) % PF], qf = rb_[(24 + st) % PF];
-            if (st + PF < 8) load_tr(1, st + PF, (24 + st) % PF);
-            dv_acc[st & 3] = mfma32(pf[2 + (st >> 2)], gf, dv_acc[st & 3]);
-            dk_acc[st & 3] = mfma32(df[2 + (st >> 2)], qf, dk_acc[st & 3]);
-            __builtin_amdgcn_sched_barrier(0);
-        }
+        xch_mine[0 * 64] = pack_bf16x8(p[0], p[1], p[2], p[3], p[4], p[5], p[6], p[7]);
+        xch_mine[1 * 64] = pack_bf16x8(p[8], p[9], p[10], p[11], p[12], p[13], p[14], p[15]);
+        xch_mine[2 * 64] = pack_bf16x8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
+        xch_mine[3 * 64] = pack_bf16x8(ds[8], ds[9], ds[10], ds[11], ds[12], ds[13], ds[14], ds[15]);
+        // the fragments must be in LDS before the barrier that ends this phase
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     };
 
-    // Tile order: first the tiles that need masking (the leading, partly visible q tiles and a ragged last
-    // tile), then the fully visible ones -- two plain loops, one instantiation of the body each.
-    const int n_all = n_qtiles - qt_begin;
+    // Phase sequence of a group: M(0) V(0) M(1) V(1) ... M(n_all), a barrier before every phase; group 1
+    // starts one barrier late and group 0 ends with one extra.  Tile i + 2 is requested in the slot in which
+    // group 0 runs M(i + 1) and group 1 runs V(i), and must have landed two slots later: both groups wait for
+    // their own transfers at the end of the phase in between.
     if (n_all > 0) {
-        const bool ragged = n_qtiles * TM > g.lq;
-        const int lead = (qt_full < n_qtiles ? qt_full : n_qtiles) - qt_begin;     // partly visible tiles
-        const bool extra = ragged && qt_begin + lead < n_qtiles;                    // ragged last tile not among them
-        const int n_masked = lead + (extra ? 1 : 0);
-        auto tile_of = [&](int i) { return i < lead ? qt_begin + i : (i < n_masked ? n_qtiles - 1 : qt_begin + lead + (i - n_masked)); };
-        fetch_tile(tile_of(0), 0);
-        // one tile: publish it (wait for this wavefront's outstanding global->LDS loads, then barrier),
-        // start fetching the next one into the other buffer, compute
-        auto step = [&](int i, auto buf_c, auto masked_c) __attribute__((always_inline)) {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-            if (i + 1 < n_all) fetch_tile(tile_of(i + 1), decltype(buf_c)::value ^ 1);
-            tile_body(buf_c, masked_c);
+        fetch_tile(0);
+        if (n_all > 1) fetch_tile(1);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (grp == 1) wg_barrier();
+        auto enter_m = [&](int i) __attribute__((always_inline)) {
+            if (grp == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            wg_barrier();
+            if (grp == 0 && i >= 1 && i + 1 < n_all) fetch_tile(i + 1);
         };
-        using B0 = std::integral_constant<int, 0>;
-        using B1 = std::integral_constant<int, 1>;
-        int i = 0;
-        // masked tiles (buffer parity follows i), then unmasked tiles two at a time
-        for (; i + 1 < n_masked; i += 2) {
-            step(i, B0{}, std::true_type{});
-            step(i + 1, B1{}, std::true_type{});
+        auto vector_part = [&](int i) __attribute__((always_inline)) {
+            if (grp == 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            wg_barrier();
+            if (grp == 1 && i + 2 < n_all) fetch_tile(i + 2);
+            if (i < n_masked) v_phase(i % NB, i & 7, std::true_type{});
+            else v_phase(i % NB, i & 7, std::false_type{});
+        };
+        enter_m(0); m_phase(IC<0>{}, IC<16>{}, IC<32>{}); vector_part(0);
+        // tiles 1 .. n_all-1: three at a time in a straight line (buffer = i % 3 is then a compile-time constant
+        // and no accumulator passes through a control-flow merge), then the remaining ones through a switch
+        int i = 1;
+        for (; i + 2 < n_all; i += 3) {
+            enter_m(i);     m_phase(IC<1>{}, IC<0>{}, IC<32>{}); vector_part(i);
+            enter_m(i + 1); m_phase(IC<2>{}, IC<0>{}, IC<32>{}); vector_part(i + 1);
+            enter_m(i + 2); m_phase(IC<0>{}, IC<0>{}, IC<32>{}); vector_part(i + 2);
         }
-        if (i < n_masked) { step(i, B0{}, std::true_type{}); ++i; }
-        if (i < n_all && (i & 1)) { step(i, B1{}, std::false_type{}); ++i; }
-        for (; i + 1 < n_all; i += 2) {
-            step(i, B0{}, std::false_type{});
-            step(i + 1, B1{}, std::false_type{});
+        for (; i < n_all; ++i) {
+            enter_m(i);
+            switch (i % NB) {
+                case 0: m_phase(IC<0>{}, IC<0>{}, IC<32>{}); break;
+                case 1: m_phase(IC<1>{}, IC<0>{}, IC<32>{}); break;
+                default: m_phase(IC<2>{}, IC<0>{}, IC<32>{}); break;
+            }
+            vector_part(i);
         }
-        if (i < n_all) step(i, B0{}, std::false_type{});
+        enter_m(n_all);
+        switch (n_all % NB) {
+            case 0: m_phase(IC<0>{}, IC<0>{}, IC<16>{}); break;
+            case 1: m_phase(IC<1>{}, IC<0>{}, IC<16>{}); break;
+            default: m_phase(IC<2>{}, IC<0>{}, IC<16>{}); break;
+        }
+        if (grp == 0) wg_barrier();
     }
-    // dK / dV: lane holds column d = 32*db + l32; register r holds key 32*wave + 8*(r/4) + 4*hh + r%4
+
+    // dK / dV: lane holds column d = 64*hd + 32*db + l32; register r holds key wcol0 + 8*(r/4) + 4*hh + r%4
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+    for (int db = 0; db < 2; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int col = col0 + 32 * wave + 8 * (r >> 2) + 4 * hh + (r & 3);
+            const int col = wcol0 + 8 * (r >> 2) + 4 * hh + (r & 3);
             if (col < g.lc) {
-                const long long idx = ((long long)col * g.nkv + kvh) * D + 32 * db + l32;
+                const long long idx = ((long long)col * g.nkv + kvh) * D + 64 * hd + 32 * db + l32;
                 const float kk = dk_acc[db][r] * g.scale, vv = dv_acc[db][r];
                 if (ATOMIC_DKV) {
                     global_atomic_add(a.dk + idx, kk);
@@ -329,7 +363,7 @@ __global__ void __launch_bounds__(256) bwd_dkdv_bf16_kernel(const BwdArgs a, con
 hipError_t hexi_launch_bwd_bf16(const BwdArgs& a, hipStream_t s)
 {
     if (a.want_dkdv) {
-        const int n_kv_tiles = (a.g.lc + TN - 1) / TN;
+        const int n_kv_tiles = (a.g.lc + WG_KEYS - 1) / WG_KEYS;
         // does any kv head serve more than one q head?  then the heads' dK/dV tiles are summed atomically
         int cnt[HEXI_MAX_HEADS] = {0};
         bool shared = false, unused = false;
@@ -342,8 +376,8 @@ hipError_t hexi_launch_bwd_bf16(const BwdArgs& a, hipStream_t s)
             if (e == hipSuccess) e = hexi_launch_fill_f32(a.dv, n, 0.f, s);
             if (e != hipSuccess) return e;
         }
-        if (shared) bwd_dkdv_bf16_kernel<true><<<grid, 256, 0, s>>>(a, n_kv_tiles);
-        else bwd_dkdv_bf16_kernel<false><<<grid, 256, 0, s>>>(a, n_kv_tiles);
+        if (shared) bwd_dkdv_bf16_kernel<true><<<grid, 512, 0, s>>>(a, n_kv_tiles);
+        else bwd_dkdv_bf16_kernel<false><<<grid, 512, 0, s>>>(a, n_kv_tiles);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
