@@ -230,3 +230,46 @@ def test_forward_is_deterministic():
     o1, l1 = run.o.clone(), run.lse.clone()
     run.forward(); torch.cuda.synchronize()
     assert torch.equal(o1, run.o) and torch.equal(l1, run.lse)
+
+
+@pytest.mark.parametrize("lq,lc", [(1, 1), (63, 65), (255, 64), (256, 129), (257, 300), (600, 192), (513, 1)])
+def test_workgroup_boundary_sizes(lq, lc):
+    # shard / chunk lengths just below, at and above the kernels' workgroup tiles (256 q rows, 128 / 64 keys):
+    # one, two and a fraction of a tile, a single row, a single key; two chunks so that the second is diagonal
+    l_tot = lc + lq
+    q_segs = [(lc, lq)]
+    chunks = [[(0, lc)], [(lc, lq)]]
+    w = _custom(f"edge_{lq}_{lc}", "bf16", 2, 1, 128, l_tot, q_segs, chunks)
+    _run_and_compare(w, seed=lq * 1000 + lc)
+
+
+def test_forward_exact_softmax_fallback():
+    # The fast forward path fixes each row's softmax reference after its first key tile and repeats the
+    # workgroup with the exact online softmax when a row's sum leaves [2^-60, 2^60].  Keys beyond the first
+    # tile are scaled so that later scores exceed the first tile's maximum by far more than 2^100 (rows 0-255,
+    # both wave groups, upward), and a second shard does the reverse (first tile huge, the rest tiny: downward
+    # is harmless but must stay exact too).  Everything is compared with the oracle.
+    dev = torch.device(DEV)
+    g = torch.Generator().manual_seed(99)
+    lq, lc, nq, d = 300, 640, 2, 128
+    for first_scale, later_scale in ((1.0, 60.0), (60.0, 0.02)):
+        q = (torch.randn((lq, nq, d), generator=g) * 3).to(torch.bfloat16)
+        k = torch.randn((lc, 1, d), generator=g)
+        k[:64] *= first_scale
+        k[64:] *= later_scale
+        k = k.to(torch.bfloat16)
+        v = torch.randn((lc, 1, d), generator=g).to(torch.bfloat16)
+        scale = d ** -0.5
+        qd, kd, vd = q.to(dev), k.to(dev), v.to(dev)
+        o = torch.zeros((lq, nq, d), dtype=torch.float32, device=dev)
+        lse = torch.full((nq, lq), float("-inf"), dtype=torch.float32, device=dev)
+        q_segs, kv_segs = [(lc, lq)], [(0, lc)]
+        hexi.hexi_attn_fwd_chunk(hexi.desc_for(qd, kd, scale), q_segs, kv_segs, qd, kd, vd, o, lse)
+        torch.cuda.synchronize()
+        o_ref, lse_ref = oracle.attn_fwd(to64(q), np.arange(lc, lc + lq), to64(k), to64(v), np.arange(lc), scale)
+        spread = float(np.max(lse_ref) - np.min(lse_ref))
+        print(f"  scales {first_scale}/{later_scale}: lse range {np.min(lse_ref):.1f} .. {np.max(lse_ref):.1f}", flush=True)
+        assert spread > 50.0     # the case really spans a wide range
+        check("o", o.cpu(), o_ref, "bf16")
+        # lse values reach the hundreds here: the absolute bound scales with them (fp32 has 24 bits)
+        check("lse", lse.cpu(), lse_ref, "bf16", abs_factor=max(1.0, float(np.max(np.abs(lse_ref))) * 1e-2))
