@@ -5,7 +5,7 @@ One step = one pass of the whole hot path over one synthetic shard: forward repl
 list (fwd_chunk with the fused LSE merge), Delta, backward replay (bwd_chunk per chunk).  Inputs are
 resident in HBM before the timed region.  Prints one JSON line: fwd+bwd TFLOP/s counted on unmasked
 (query, key) pairs only (4*d forward + 10*d backward flops per pair per q head), the roofline
-position of the dominant kernel (the bf16 backward kernel) measured with HIP events around its
+position of the dominant kernel (the bf16 dK/dV backward kernel) measured with HIP events around its
 launches inside the timed region, and the fp64 CPU oracle timed on a bounded sample of the same
 workload as a reported baseline.
 """
@@ -19,7 +19,7 @@ import torch
 PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16 MFMA peak: 256 CU x 2.4 GHz x 4096 flop/clk/CU
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # command (see profiles/); None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {"cfg2_3b_zigzag": 1.014e9}   # bwd_dkdv_bf16_kernel: 611 MB fetched + 403 MB written
+MEASURED_TRAFFIC_BYTES = {"cfg2_3b_zigzag": 1.128e9}   # bwd_dkdv_bf16_kernel: 634 MB fetched + 494 MB written
 
 
 def parse():
