@@ -130,9 +130,12 @@ int hexi_attn_merge_lse(int64_t n_rows, int32_t n_q_heads, int32_t head_dim,
  * delta for the whole shard before the chunk is processed); otherwise delta is an input.
  * dq_acc (fp32) accumulates over calls: the caller zeroes it before the first chunk.  Each dq row is
  * updated by one workgroup per call in a fixed order (bf16 path), so dq is reproducible run to run.
- * dk, dv (fp32, this chunk's rows) are overwritten, or added to under HEXI_ACCUMULATE; when several
- * local q heads share a kv head their contributions are summed with floating-point atomics, whose
- * order (and so the last bits of dk/dv) can vary between runs.  HEXI_SKIP_DQ / HEXI_SKIP_DKDV
+ * dk, dv (fp32, this chunk's rows) are overwritten, or added to under HEXI_ACCUMULATE.  The local q
+ * heads that share a kv head are summed inside one workgroup when the launch is large enough
+ * without splitting them (dk/dv are then reproducible run to run); otherwise groups are cut into
+ * runs of heads whose contributions are summed with floating-point atomics, whose order (and so
+ * the last bits of dk/dv) can vary between runs.  The environment variable HEXI_DKDV_RUN_LEN
+ * (>= 1) overrides the run length chosen by the library.  HEXI_SKIP_DQ / HEXI_SKIP_DKDV
  * restrict the call to one of the two halves (they are separate kernels and may be issued on
  * different streams); both set is HEXI_EINVAL.  A chunk
  * wholly in the shard's future writes zeros to dk/dv (nothing under HEXI_ACCUMULATE) and leaves

@@ -24,9 +24,12 @@
 // start of its vector phase, dO (+ LSE, Delta) by group 0 at the start of the matrix phase it runs in the
 // same slot.
 //
-// The q heads of a GQA group run in different workgroups and add their dK / dV tiles with fp32 atomics (plain
-// stores when the group has a single head), so dk/dv must be zero-filled (or hold the running sum under
-// HEXI_ACCUMULATE) before the launch.
+// GQA: the q heads that read one kv head are cut into runs; a workgroup walks the q tiles of all heads of its
+// run, one head after the other, into the same dK / dV accumulators (the K / V fragments are loaded once per
+// run).  When a kv head has a single run its tiles are written with plain stores; otherwise the runs add theirs
+// with fp32 atomics, and dk/dv must be zero-filled (or hold the running sum under HEXI_ACCUMULATE) before the
+// launch.  The host picks the run length: as long as possible while the launch still has a few workgroups per CU.
+#include <cstdlib>
 #include "hexi_internal.h"
 #include "hexi_mfma.h"
 
@@ -53,8 +56,15 @@ struct BwdSmem {
 // one row read from 16 on
 __host__ __device__ constexpr int reads_of(int st) { return st < 16 ? 2 + ((st & 1) == 0 ? 1 : 0) : 1; }
 
+// Runs of q heads: run r covers len[r] heads starting at first[r], linked through next[] (all read kv head
+// kv_of_q[first[r]]).
+struct HeadRuns {
+    int n;
+    signed char first[HEXI_MAX_HEADS], len[HEXI_MAX_HEADS], next[HEXI_MAX_HEADS];
+};
+
 template <bool ATOMIC_DKV>
-__global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, const int n_kv_tiles)
+__global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, const HeadRuns runs, const int n_kv_tiles)
 {
     const AttnGeom& g = a.g;
     __shared__ __attribute__((aligned(1024))) BwdSmem sm;
@@ -66,29 +76,26 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
     const int grp2 = (lane >> 4) & 1, j16 = lane & 15;
 
     // Work mapping: consecutive workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a contiguous
-    // range of (head, key tile) units so that the workgroups sharing an L2 stream the same head's Q / dO tiles.
-    const int n_units = g.nq * n_kv_tiles;
+    // range of (head run, key tile) units so that the workgroups sharing an L2 stream the same heads' Q / dO tiles.
+    const int n_units = runs.n * n_kv_tiles;
     int unit;
     {
         const int per = n_units / 8, rem = n_units % 8;
         const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
         unit = xcd * per + (xcd < rem ? xcd : rem) + slot;
     }
-    const int h = unit / n_kv_tiles;
-    const int kv_tile = unit - h * n_kv_tiles;
-    const int kvh = g.kv_of_q[h];
+    const int run = unit / n_kv_tiles;
+    const int kv_tile = unit - run * n_kv_tiles;
+    const int n_heads = runs.len[run];
+    const int kvh = g.kv_of_q[runs.first[run]];
     const int col0 = kv_tile * WG_KEYS;
     const int wcol0 = col0 + 64 * grp + 32 * pair;     // first key of this wavefront pair
     const int my_col = wcol0 + l32;
     const int my_col_c = my_col < g.lc ? my_col : g.lc - 1;
     const int my_kpos = my_col < g.lc ? seg_pos_of_row(g.ks, my_col) : 0x7fffffff;
 
-    const uint16_t* q = static_cast<const uint16_t*>(a.q) + (long long)h * g.q_stride_head;
-    const uint16_t* go = static_cast<const uint16_t*>(a.d_o) + (long long)h * g.q_stride_head;
     const uint16_t* k = static_cast<const uint16_t*>(a.k) + (long long)kvh * g.kv_stride_head;
     const uint16_t* v = static_cast<const uint16_t*>(a.v) + (long long)kvh * g.kv_stride_head;
-    const float* lse_h = a.lse + (long long)h * g.lq;
-    const float* delta_h = a.delta + (long long)h * g.lq;
 
     // q rows that see at least one key of the workgroup's tile form a suffix of the shard; rows that see all of
     // its keys form a (shorter) suffix
@@ -119,9 +126,11 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
         for (int r = 0; r < 16; ++r) { dk_acc[db][r] = 0.f; dv_acc[db][r] = 0.f; }
     const float scale_log2 = g.scale * LOG2E;
 
-    // Tile order: first the tiles that need masking (the leading, partly visible q tiles and a ragged last
-    // tile), then the fully visible ones.
+    // Tile order within a head: first the tiles that need masking (the leading, partly visible q tiles and a
+    // ragged last tile), then the fully visible ones.  The workgroup's tile sequence is that order repeated for
+    // every head of the run: n_seq tiles, numbered i = 0 .. n_seq - 1 below.
     const int n_all = n_qtiles - qt_begin;
+    const int n_seq = n_all > 0 ? n_all * n_heads : 0;
     const bool ragged = n_qtiles * TM > g.lq;
     const int lead = n_all > 0 ? (qt_full < n_qtiles ? qt_full : n_qtiles) - qt_begin : 0;     // partly visible tiles
     const bool extra = ragged && qt_begin + lead < n_qtiles;                                    // ragged last tile not among them
@@ -149,14 +158,21 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
     const uint32_t lds_q = (uint32_t)(uintptr_t)(&sm.q[0][0]), lds_g = (uint32_t)(uintptr_t)(&sm.g[0][0]);
     const uint32_t lds_dump = (uint32_t)(uintptr_t)(&sm.dump[0]);
     const uint32_t lds_lse = (uint32_t)(uintptr_t)(&sm.lse[0][0]), lds_delta = (uint32_t)(uintptr_t)(&sm.delta[0][0]);
-    const uint16_t* fetch_src = grp ? q : go;
+    const uint16_t* fetch_src = static_cast<const uint16_t*>(grp ? a.q : a.d_o);
     const uint32_t fetch_lds = grp ? lds_q : lds_g;
-    auto fetch_tile = [&](int i) {     // i: index in processing order; buffer i % NB
-        const int qt = tile_of(i);
+    // Tiles are requested in sequence order by every wavefront; (fetch_t, fetch_h) is the next one's tile
+    // index within its head and its head.
+    int fetch_t = 0, fetch_h = runs.first[run];
+    auto fetch_tile = [&](int i) {     // i: index in the sequence; buffer i % NB
+        const int qt = tile_of(fetch_t);
+        const bool needs_mask = fetch_t < n_masked;
         const int row0 = qt * TM;
         const int buf = i % NB;
         const uint32_t dst = __builtin_amdgcn_readfirstlane(fetch_lds + buf * P16_TILE_BYTES + wg4 * 1024);
-        const uint16_t* src = fetch_src + (long long)row0 * g.q_stride_tok;
+        const uint16_t* src = fetch_src + (long long)fetch_h * g.q_stride_head + (long long)row0 * g.q_stride_tok;
+        const float* lse_h = a.lse + (long long)fetch_h * g.lq;
+        const float* delta_h = a.delta + (long long)fetch_h * g.lq;
+        if (++fetch_t == n_all) { fetch_t = 0; fetch_h = runs.next[fetch_h]; }
         if (row0 + TM <= g.lq) {
 #pragma unroll
             for (int t = 0; t < DMA_PER_WAVE; ++t) {
@@ -179,7 +195,7 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
                 const float* src4 = (wg4 == 0 ? lse_h : delta_h) + row;
                 lds_dma4(src4, __builtin_amdgcn_readfirstlane((wg4 == 0 ? lds_lse : lds_delta) + buf * (TM * 4)));
             }
-        } else if (wg4 == 0 && i < n_masked) {
+        } else if (wg4 == 0 && needs_mask) {
             // global positions of the tile's rows, only for tiles that need masking
             sm.qpos[i & 7][lane] = row0 + lane < g.lq ? seg_pos_of_row(g.qs, row0 + lane) : -1;
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -289,37 +305,39 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     };
 
-    // Phase sequence of a group: M(0) V(0) M(1) V(1) ... M(n_all), a barrier before every phase; group 1
+    // Phase sequence of a group: M(0) V(0) M(1) V(1) ... M(n_seq), a barrier before every phase; group 1
     // starts one barrier late and group 0 ends with one extra.  Tile i + 2 is requested in the slot in which
     // group 0 runs M(i + 1) and group 1 runs V(i), and must have landed two slots later: both groups wait for
     // their own transfers at the end of the phase in between.
-    if (n_all > 0) {
+    if (n_seq > 0) {
+        int proc_t = 0;     // tile index within its head of the tile in the vector phase
         fetch_tile(0);
-        if (n_all > 1) fetch_tile(1);
+        if (n_seq > 1) fetch_tile(1);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         if (grp == 1) wg_barrier();
         auto enter_m = [&](int i) __attribute__((always_inline)) {
             if (grp == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             wg_barrier();
-            if (grp == 0 && i >= 1 && i + 1 < n_all) fetch_tile(i + 1);
+            if (grp == 0 && i >= 1 && i + 1 < n_seq) fetch_tile(i + 1);
         };
         auto vector_part = [&](int i) __attribute__((always_inline)) {
             if (grp == 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             wg_barrier();
-            if (grp == 1 && i + 2 < n_all) fetch_tile(i + 2);
-            if (i < n_masked) v_phase(i % NB, i & 7, std::true_type{});
+            if (grp == 1 && i + 2 < n_seq) fetch_tile(i + 2);
+            if (proc_t < n_masked) v_phase(i % NB, i & 7, std::true_type{});
             else v_phase(i % NB, i & 7, std::false_type{});
+            if (++proc_t == n_all) proc_t = 0;
         };
         enter_m(0); m_phase(IC<0>{}, IC<16>{}, IC<32>{}); vector_part(0);
-        // tiles 1 .. n_all-1: three at a time in a straight line (buffer = i % 3 is then a compile-time constant
+        // tiles 1 .. n_seq-1: three at a time in a straight line (buffer = i % 3 is then a compile-time constant
         // and no accumulator passes through a control-flow merge), then the remaining ones through a switch
         int i = 1;
-        for (; i + 2 < n_all; i += 3) {
+        for (; i + 2 < n_seq; i += 3) {
             enter_m(i);     m_phase(IC<1>{}, IC<0>{}, IC<32>{}); vector_part(i);
             enter_m(i + 1); m_phase(IC<2>{}, IC<0>{}, IC<32>{}); vector_part(i + 1);
             enter_m(i + 2); m_phase(IC<0>{}, IC<0>{}, IC<32>{}); vector_part(i + 2);
         }
-        for (; i < n_all; ++i) {
+        for (; i < n_seq; ++i) {
             enter_m(i);
             switch (i % NB) {
                 case 0: m_phase(IC<0>{}, IC<0>{}, IC<32>{}); break;
@@ -328,8 +346,8 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
             }
             vector_part(i);
         }
-        enter_m(n_all);
-        switch (n_all % NB) {
+        enter_m(n_seq);
+        switch (n_seq % NB) {
             case 0: m_phase(IC<0>{}, IC<0>{}, IC<16>{}); break;
             case 1: m_phase(IC<1>{}, IC<0>{}, IC<16>{}); break;
             default: m_phase(IC<2>{}, IC<0>{}, IC<16>{}); break;
@@ -364,20 +382,67 @@ hipError_t hexi_launch_bwd_bf16(const BwdArgs& a, hipStream_t s)
 {
     if (a.want_dkdv) {
         const int n_kv_tiles = (a.g.lc + WG_KEYS - 1) / WG_KEYS;
-        // does any kv head serve more than one q head?  then the heads' dK/dV tiles are summed atomically
+        // q heads per kv head, in head order
         int cnt[HEXI_MAX_HEADS] = {0};
-        bool shared = false, unused = false;
-        for (int h = 0; h < a.g.nq; ++h) shared |= (++cnt[a.g.kv_of_q[h]] > 1);
+        int max_cnt = 0;
+        bool unused = false;
+        for (int h = 0; h < a.g.nq; ++h) {
+            const int c = ++cnt[a.g.kv_of_q[h]];
+            max_cnt = c > max_cnt ? c : max_cnt;
+        }
         for (int kh = 0; kh < a.g.nkv; ++kh) unused |= (cnt[kh] == 0);   // a kv head no local q head reads: zero gradient
-        const unsigned grid = (unsigned)(a.g.nq * n_kv_tiles);
+        // Run length: the longest divisor of the largest group's size (so that its runs are equally long) for which
+        // the launch still has about three workgroups per CU and a workgroup walks at most 512 q tiles.  A run
+        // amortises the workgroup's prologue and epilogue (about 20 tiles' worth) and, when it covers the whole
+        // group, needs no atomics; but the workgroups of an XCD stream the same Q / dO tiles only while they stay
+        // in step, and long tile sequences let them drift apart (measured: more L2 misses, slower launches).
+        auto n_runs_for = [&](int len) {
+            int n = 0;
+            for (int kh = 0; kh < a.g.nkv; ++kh) n += (cnt[kh] + len - 1) / len;
+            return n;
+        };
+        // q tiles that see the chunk's first key: the longest tile sequence of one head
+        const int n_qtiles = (a.g.lq + TM - 1) / TM;
+        const int max_tiles = a.g.lc > 0 ? n_qtiles - seg_rows_le(a.g.qs, seg_pos_of_row(a.g.ks, 0) - 1) / TM : 0;
+        int run_len = max_cnt;
+        while (run_len > 1 && (max_cnt % run_len != 0 || (long long)run_len * max_tiles > 512 ||
+                               (long long)n_runs_for(run_len) * n_kv_tiles < 3 * 256))
+            --run_len;
+        if (const char* forced = getenv("HEXI_DKDV_RUN_LEN")) {     // tuning / test override of the heuristic
+            const int v = atoi(forced);
+            if (v >= 1) run_len = v < max_cnt ? v : max_cnt;
+        }
+        HeadRuns runs;
+        runs.n = 0;
+        int last[HEXI_MAX_HEADS], open_run[HEXI_MAX_HEADS];   // per kv head: its last q head so far, its run being filled
+        bool shared = false;
+        for (int kh = 0; kh < a.g.nkv; ++kh) { last[kh] = -1; open_run[kh] = -1; }
+        for (int h = 0; h < a.g.nq; ++h) {
+            const int kh = a.g.kv_of_q[h];
+            runs.next[h] = -1;
+            if (open_run[kh] >= 0 && runs.len[open_run[kh]] < run_len) {
+                runs.next[last[kh]] = (signed char)h;
+                ++runs.len[open_run[kh]];
+            } else {
+                shared |= open_run[kh] >= 0;     // a second run on this kv head: the runs add their tiles atomically
+                open_run[kh] = runs.n;
+                runs.first[runs.n] = (signed char)h;
+                runs.len[runs.n] = 1;
+                ++runs.n;
+            }
+            last[kh] = h;
+        }
+        const unsigned grid = (unsigned)(runs.n * n_kv_tiles);
         if ((shared || unused) && !a.accumulate) {
             const long long n = (long long)a.g.lc * a.g.nkv * D;
             hipError_t e = hexi_launch_fill_f32(a.dk, n, 0.f, s);
             if (e == hipSuccess) e = hexi_launch_fill_f32(a.dv, n, 0.f, s);
             if (e != hipSuccess) return e;
         }
-        if (shared) bwd_dkdv_bf16_kernel<true><<<grid, 512, 0, s>>>(a, n_kv_tiles);
-        else bwd_dkdv_bf16_kernel<false><<<grid, 512, 0, s>>>(a, n_kv_tiles);
+        if (grid > 0) {
+            if (shared) bwd_dkdv_bf16_kernel<true><<<grid, 512, 0, s>>>(a, runs, n_kv_tiles);
+            else bwd_dkdv_bf16_kernel<false><<<grid, 512, 0, s>>>(a, runs, n_kv_tiles);
+        }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

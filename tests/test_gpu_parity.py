@@ -112,6 +112,21 @@ def test_explicit_head_map_and_single_rows():
     _run_and_compare(w, seed=12)
 
 
+@pytest.mark.parametrize("run_len", [1, 2, 3, 8])
+def test_dkdv_head_runs(run_len, monkeypatch):
+    # The dK/dV kernel walks runs of q heads that share a kv head in one workgroup; the launcher picks the
+    # run length from the launch size, so small shapes would only ever see runs of one head.  Force the
+    # length: whole groups (no atomics), runs with a remainder (3 of 5), non-adjacent heads of a group,
+    # groups of unequal size, masked + full + ragged tiles in every head of a run.
+    monkeypatch.setenv("HEXI_DKDV_RUN_LEN", str(run_len))
+    w = _custom(f"runs{run_len}", "bf16", 8, 3, 128, 700, [(150, 70), (400, 300)], [[(0, 333)], [(333, 367)]],
+                kv_of_q=[0, 1, 0, 0, 2, 0, 1, 0])
+    _run_and_compare(w, seed=21)
+    # one group of 8 heads over several key tiles, unfused path
+    w = _custom(f"runs{run_len}_hp", "bf16", 8, 1, 128, 1024, [(512, 512)], [[(0, 512)], [(512, 512)]])
+    _run_and_compare(w, seed=22, fused=False)
+
+
 def test_strided_inputs_and_accumulate_flags():
     # q/dO and k/v are slices of wider buffers (token and head strides larger than dense)
     w = _custom("strided", "bf16", 4, 2, 128, 512, [(128, 384)], [[(0, 256)], [(256, 256)]])
