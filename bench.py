@@ -19,7 +19,7 @@ import torch
 PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16 MFMA peak: 256 CU x 2.4 GHz x 4096 flop/clk/CU
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # command (see profiles/); None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {"cfg2_3b_zigzag": 1.128e9}   # bwd_dkdv_bf16_kernel: 634 MB fetched + 494 MB written
+MEASURED_TRAFFIC_BYTES = {"cfg2_3b_zigzag": 0.650e9}   # bwd_dkdv_bf16_kernel<false>: 486 MB fetched + 164 MB written
 
 
 def parse():
@@ -103,7 +103,8 @@ def main():
 
     # dominant kernel: the dK/dV half of the backward step.  Per launch its algorithmic work is the four
     # matmuls S = QK^T, dP = dO V^T, dV = P^T dO, dK = dS^T Q on the unmasked pairs: 8*d*nq*(pairs of that chunk).
-    # (With GQA the event pair also covers the two zero-fills of dk/dv that precede the kernel.)
+    # (When the launcher splits a GQA group over several workgroups the event pair also covers the two
+    # zero-fills of dk/dv that precede the kernel.)
     if kern_ev:
         k_ms = sum(a.elapsed_time(b) for _, a, b in kern_ev) / len(kern_ev)
         k_flops = sum(8.0 * d * nq * n_pairs_chunk[j] for j, _, _ in kern_ev) / len(kern_ev)
