@@ -99,6 +99,7 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     fwd_ms = sum(a.elapsed_time(b) for a, b in fwd_ev) / args.steps
     bwd_ms = sum(a.elapsed_time(b) for a, b in bwd_ev) / args.steps
+    step_ms = sorted(f[0].elapsed_time(b[1]) for f, b in zip(fwd_ev, bwd_ev))     # per-step device time
     tflops = (flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12
 
     # dominant kernel: the dK/dV half of the backward step.  Per launch its algorithmic work is the four
@@ -126,17 +127,65 @@ def main():
                       "q_rows": w.lq, "kv_chunks": len(w.chunks), "unmasked_pairs_per_head": n_pairs,
                       "counted_tflop_per_step": round((flops_fwd + flops_bwd) / 1e12, 3)},
            "pct_of_bf16_mfma_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
+           "step_ms_min": round(step_ms[0], 4), "step_ms_median": round(step_ms[len(step_ms) // 2], 4),
            "fwd_ms": round(fwd_ms, 4), "bwd_ms": round(bwd_ms, 4),
            "fwd_tflops": round(flops_fwd / (fwd_ms * 1e-3) / 1e12, 2),
            "bwd_tflops": round(flops_bwd / (bwd_ms * 1e-3) / 1e12, 2),
            "roofline": roofline}
 
+    # The paper's own cost convention (App. A.4, Eq. 11): 16 * L_q * L_src * n_d * d_h per ring step, no causal
+    # discount, recomputation counted as a separate pass; summed here over the steps that see at least one key.
+    paper_flops = sum(16.0 * w.lq * sum(n for _, n in w.chunks[j]) * nq * d for j in live)
+    out["paper_convention"] = {"tflop_per_step": round(paper_flops / 1e12, 3),
+                               "tflops": round(paper_flops / (ms_per_step * 1e-3) / 1e12, 2),
+                               "note": "16*Lq*Lc*nq*d per live ring step (App. A.4 Eq. 11), masked pairs included"}
+    out["hbm_bound_kernels"] = hbm_bound_kernels(run, w)
+
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, inputs, args.cpu_rows)
+        out["cpu_baseline"] = cpu_baseline(w, inputs, args.cpu_rows, n_pairs)
     print(json.dumps(out), flush=True)
 
 
-def cpu_baseline(w, inputs, rows_per_seg):
+def hbm_bound_kernels(run, w, reps=10):
+    """The two elementwise steps of the path, outside the timed region: the Delta prepass (reads o fp32 and dO,
+    writes Delta) and the unfused two-term LSE merge (reads both partials, writes the accumulator), each
+    against the 8 TB/s HBM roof with its algorithmic bytes."""
+    from paper_2605_07569_amd import hexi
+    lq, nq, d = w.lq, w.n_q_heads, w.head_dim
+    esz = 2 if w.dtype == "bf16" else 4
+    o_part, lse_part = torch.zeros_like(run.o), torch.zeros_like(run.lse)
+    o_acc, lse_acc = run.o.clone(), run.lse.clone()
+
+    def timed(fn):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    merge_ms = timed(lambda: hexi.hexi_attn_merge_lse(o_acc, lse_acc, o_part, lse_part))
+    merge_bytes = 3.0 * lq * nq * (4 * d + 4)            # read accumulator + partial, write accumulator
+    # Delta alone: a backward call with HEXI_COMPUTE_DELTA on a one-key chunk that lies in the shard's future
+    # (the call then only fills Delta and zeroes one row of dk/dv)
+    last_pos = max(st + n for st, n in w.q_segs)
+    k1, v1 = run.k[0][:1].contiguous(), run.v[0][:1].contiguous()
+    dk1, dv1 = torch.empty((1, w.n_kv_heads, d), dtype=torch.float32, device=run.dev), torch.empty((1, w.n_kv_heads, d), dtype=torch.float32, device=run.dev)
+    desc1 = hexi.desc_for(run.q, k1, w.scale, w.kv_of_q)
+    delta_ms = timed(lambda: hexi.hexi_attn_bwd_chunk(desc1, w.q_segs, [(last_pos, 1)], run.q, k1, v1, run.o, run.d_o, run.lse,
+                                                      run.delta, run.dq, dk1, dv1, flags=hexi.HEXI_COMPUTE_DELTA))
+    delta_bytes = float(lq) * nq * (d * (4 + esz) + 4)   # read o (fp32) and dO, write Delta
+    res = {"merge_lse": {"ms": round(merge_ms, 4), "GB/s": round(merge_bytes / merge_ms / 1e6, 1),
+                         "frac_of_8TBps": round(merge_bytes / merge_ms / 1e6 / 8000.0, 3)}}
+    if delta_ms > 0:
+        res["delta"] = {"ms": round(delta_ms, 4), "GB/s": round(delta_bytes / delta_ms / 1e6, 1),
+                        "frac_of_8TBps": round(delta_bytes / delta_ms / 1e6 / 8000.0, 3)}
+    return res
+
+
+def cpu_baseline(w, inputs, rows_per_seg, n_pairs_full=None):
     """The fp64 oracle, as it stands, on a bounded sample: a few rows of every q segment, all local
     heads, each row against all its visible keys, forward + backward.  Rate in the metric's unit,
     counting the same 14*d flops per unmasked pair."""
@@ -167,7 +216,10 @@ def cpu_baseline(w, inputs, rows_per_seg):
     dt = time.perf_counter() - t0
     pairs = float(np.sum(q_pos + 1))
     flops = 14.0 * w.head_dim * pairs * w.n_q_heads
-    return {"value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+    extra = {}
+    if n_pairs_full:
+        extra["extrapolated_full_seconds"] = round(dt * n_pairs_full / pairs, 0)    # an extrapolation, not a measurement
+    return {**extra, "value": round(flops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
             "sample": f"{len(rows)} of {w.lq} shard rows (evenly spaced in each q segment) x all {w.n_q_heads} local heads, "
                       f"each against all its visible keys, fwd+bwd in fp64; {dt:.1f} s",
             "seconds": round(dt, 2)}
