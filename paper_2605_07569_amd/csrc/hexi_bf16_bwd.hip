@@ -39,7 +39,7 @@ constexpr int D = 128;
 constexpr int WG_KEYS = 128;     // keys per workgroup: 2 groups x 2 pairs x 32
 constexpr int TM = 64;           // q rows per tile
 constexpr int NB = 3;            // LDS buffers per tensor
-constexpr int DMA_PER_WAVE = 5;  // tile transfers per wavefront per tile (17 real ones per tile, 3 dummies)
+constexpr int DMA_PER_WAVE = 5;  // most tile transfers a wavefront issues per tile (17 per tile over 4 wavefronts)
 constexpr float LOG2E = 1.4426950408889634f;
 
 struct BwdSmem {
@@ -49,7 +49,6 @@ struct BwdSmem {
     float lse[NB][TM];
     float delta[NB][TM];
     int qpos[8][TM];                       // row positions of the tiles that need a mask, written two tiles ahead
-    unsigned char dump[1024];              // destination of the dummy transfers
 };
 
 // LDS reads of matrix-phase step st: two transposed reads (+ one P^T / dS^T fragment on even steps) below 16,
@@ -140,8 +139,8 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
     // Direct global->LDS fetch of one 64-row tile by the four wavefronts of a group (group 1: Q, group 0: dO).
     // A transfer is one wave-wide instruction: lane L writes the 16 bytes at (transfer * 1024 + 16 * L) of the
     // tile's LDS image and reads the 16-byte piece of the q row that belongs there (the pad piece re-reads
-    // piece 0).  Wavefront wg4 issues transfers wg4, wg4 + 4, ..., wg4 + 16; transfer numbers past the tile's
-    // end go to a dump area.
+    // piece 0).  Wavefront wg4 issues the transfers wg4, wg4 + 4, ... below the tile's
+    // transfer count (5 or 4 of them).
     constexpr int N_XFER = P16_TILE_BYTES / 1024;
     uint32_t fetch_off[DMA_PER_WAVE];   // byte offsets from the tile's first row
     int fetch_row[DMA_PER_WAVE];
@@ -156,7 +155,6 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
         fetch_off[i] = 2u * (uint32_t)(r * (int)g.q_stride_tok + c * 8);
     }
     const uint32_t lds_q = (uint32_t)(uintptr_t)(&sm.q[0][0]), lds_g = (uint32_t)(uintptr_t)(&sm.g[0][0]);
-    const uint32_t lds_dump = (uint32_t)(uintptr_t)(&sm.dump[0]);
     const uint32_t lds_lse = (uint32_t)(uintptr_t)(&sm.lse[0][0]), lds_delta = (uint32_t)(uintptr_t)(&sm.delta[0][0]);
     const uint16_t* fetch_src = static_cast<const uint16_t*>(grp ? a.q : a.d_o);
     const uint32_t fetch_lds = grp ? lds_q : lds_g;
@@ -176,16 +174,14 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
         if (row0 + TM <= g.lq) {
 #pragma unroll
             for (int t = 0; t < DMA_PER_WAVE; ++t) {
-                const uint32_t d = wg4 + 4 * t < N_XFER ? dst + t * 4096 : lds_dump;
-                lds_dma16_base(src, fetch_off[t], __builtin_amdgcn_readfirstlane(d));
+                if (wg4 + 4 * t < N_XFER) lds_dma16_base(src, fetch_off[t], __builtin_amdgcn_readfirstlane(dst + t * 4096));
             }
         } else {   // ragged last tile: clamp the row index (the extra rows are masked out through their position)
 #pragma unroll
             for (int t = 0; t < DMA_PER_WAVE; ++t) {
                 uint32_t off = fetch_off[t];
                 if (row0 + fetch_row[t] >= g.lq) off -= 2u * (uint32_t)((row0 + fetch_row[t] - (g.lq - 1)) * (int)g.q_stride_tok);
-                const uint32_t d = wg4 + 4 * t < N_XFER ? dst + t * 4096 : lds_dump;
-                lds_dma16_base(src, off, __builtin_amdgcn_readfirstlane(d));
+                if (wg4 + 4 * t < N_XFER) lds_dma16_base(src, off, __builtin_amdgcn_readfirstlane(dst + t * 4096));
             }
         }
         if (grp == 0) {

@@ -28,7 +28,7 @@ constexpr int NB = 4;              // LDS buffers per tensor
 constexpr int GROUP_ROWS = 128;    // q rows per wavefront group (32 per wavefront)
 constexpr int WG_ROWS = 256;       // q rows per workgroup
 constexpr int AHEAD = 3;           // tile j + 3 is requested during tile j
-constexpr int DMA_PER_WAVE = 5;    // transfers per wavefront per tile (17 real ones per tile, 3 dummies)
+constexpr int DMA_PER_WAVE = 5;    // most transfers a wavefront issues per tile (17 per tile over 4 wavefronts)
 constexpr int STAGE_STRIDE = D + 4;   // floats per staged output row (epilogue)
 constexpr float LOG2E = 1.4426950408889634f;
 
@@ -36,7 +36,6 @@ struct DqSmem {
     unsigned char k[NB][P16_TILE_BYTES];   // 4 x 17 KB
     unsigned char v[NB][P16_TILE_BYTES];   // 4 x 17 KB
     int kpos[2 * NB][TN];     // key positions of the tiles that need a mask, written AHEAD tiles ahead
-    unsigned char dump[1024]; // destination of the dummy transfers
     // the epilogue stages 8 x (32 x 132) floats over the start of this struct
 };
 static_assert(sizeof(DqSmem) >= 8 * 32 * STAGE_STRIDE * 4, "epilogue staging does not fit");
@@ -105,9 +104,10 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
     // Direct global->LDS fetch of one tile by the four wavefronts of a group (group 1: K, group 0: V).  A
     // transfer is one wave-wide instruction: lane L writes the 16 bytes at (transfer * 1024 + 16 * L) of the
     // tile's LDS image and reads the 16-byte piece of the key row that belongs there (the pad piece re-reads
-    // piece 0).  Wavefront wg issues transfers wg, wg + 4, ..., wg + 16; transfer numbers past the tile's end
-    // go to a dump area.
+    // piece 0).  Wavefront wg issues the transfers wg, wg + 4, ... below the tile's transfer count (5 or 4
+    // of them).
     constexpr int N_XFER = P16_TILE_BYTES / 1024;
+    const int my_xfers = (N_XFER - wg + 3) / 4;     // transfers this wavefront issues per tile: wg, wg + 4, ... (5 or 4)
     uint32_t fetch_off[DMA_PER_WAVE];   // byte offsets from the tile's first key
     int fetch_row[DMA_PER_WAVE];
 #pragma unroll
@@ -121,7 +121,6 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
         fetch_off[i] = 2u * (uint32_t)(r * (int)g.kv_stride_tok + c * 8);
     }
     const uint32_t lds_k = (uint32_t)(uintptr_t)(&sm.k[0][0]), lds_v = (uint32_t)(uintptr_t)(&sm.v[0][0]);
-    const uint32_t lds_dump = (uint32_t)(uintptr_t)(&sm.dump[0]);
     const uint16_t* fetch_src = grp ? k : v;
     const uint32_t fetch_lds = grp ? lds_k : lds_v;
     auto fetch_tile = [&](int tile) {
@@ -131,16 +130,14 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
         if (col0 + TN <= g.lc) {
 #pragma unroll
             for (int i = 0; i < DMA_PER_WAVE; ++i) {
-                const uint32_t d = wg + 4 * i < N_XFER ? dst + i * 4096 : lds_dump;
-                lds_dma16_base(src, fetch_off[i], __builtin_amdgcn_readfirstlane(d));
+                if (wg + 4 * i < N_XFER) lds_dma16_base(src, fetch_off[i], __builtin_amdgcn_readfirstlane(dst + i * 4096));
             }
         } else {   // ragged last tile: clamp the key index (the extra keys are masked through their position)
 #pragma unroll
             for (int i = 0; i < DMA_PER_WAVE; ++i) {
                 uint32_t off = fetch_off[i];
                 if (col0 + fetch_row[i] >= g.lc) off -= 2u * (uint32_t)((col0 + fetch_row[i] - (g.lc - 1)) * (int)g.kv_stride_tok);
-                const uint32_t d = wg + 4 * i < N_XFER ? dst + i * 4096 : lds_dump;
-                lds_dma16_base(src, off, __builtin_amdgcn_readfirstlane(d));
+                if (wg + 4 * i < N_XFER) lds_dma16_base(src, off, __builtin_amdgcn_readfirstlane(dst + i * 4096));
             }
         }
         // global positions of the tile's keys, for the tiles some row needs a mask for
@@ -254,7 +251,7 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
     // group 0 enters M of its first block: group 0 (V) waits there, group 1 (K) waits before the vector phase
     // it runs in that same slot, V(2j - 1).  At that point tiles up to min(j + 2, NT - 1) have been requested.
     auto need_tile = [&](int j) __attribute__((always_inline)) {
-        if (j < NT) wait_tiles_in_flight((j + 2 < NT - 1 ? j + 2 : NT - 1) - j);
+        if (j < NT) wait_tiles_in_flight((j + 2 < NT - 1 ? j + 2 : NT - 1) - j, my_xfers);
     };
     auto enter_m = [&](int blk) __attribute__((always_inline)) {
         if (grp == 0 && (blk & 1) == 0) need_tile(blk >> 1);

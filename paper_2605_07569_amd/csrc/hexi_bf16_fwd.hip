@@ -43,7 +43,7 @@ constexpr int WG_ROWS = 256;       // q rows per workgroup
 constexpr int K_ROW_BYTES = 272, V_ROW_BYTES = 320;
 constexpr int K_TILE_BYTES = TN * K_ROW_BYTES;   // 17 KB = 17 wave-wide 1 KB transfers
 constexpr int V_TILE_BYTES = TN * V_ROW_BYTES;   // 20 KB = 20 transfers
-constexpr int DMA_PER_WAVE = 5;                  // transfers per wavefront per tile (K: 3 of the 20 slots are dummies)
+constexpr int DMA_PER_WAVE = 5;                  // most transfers a wavefront issues per tile (K: 17 transfers, V: 20, over 4 wavefronts)
 constexpr int O_STAGE_STRIDE = D + 4;   // floats per staged output row (epilogue)
 constexpr int K_AHEAD = 4;         // group 1 fetches K(t + 4) during V(t)
 constexpr int V_AHEAD = 2;         // group 0 fetches V(t + 2) during V(t)
@@ -60,7 +60,6 @@ struct FwdSmem {
     unsigned char k[NB][K_TILE_BYTES];   // 4 x 17 KB
     unsigned char v[NB][V_TILE_BYTES];   // 4 x 20 KB
     int kpos[2 * NB][TN];     // key positions of the tiles that need a mask, written K_AHEAD tiles ahead
-    unsigned char dump[1024]; // destination of the dummy transfers
     // the epilogue stages 8 x (32 x 132 + 32) floats over the start of this struct
 };
 static_assert(sizeof(FwdSmem) >= 8 * (32 * O_STAGE_STRIDE + 32) * 4, "epilogue staging does not fit");
@@ -122,10 +121,12 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
     // Direct global->LDS fetch of one tile by the four wavefronts of a group.  A transfer is one wave-wide
     // instruction: lane L writes the 16 bytes at (transfer * 1024 + 16 * L) of the tile's LDS image and reads
     // them from wherever the kernel points it, here the 16-byte piece of the key row that belongs there (pad
-    // pieces re-read piece 0).  Wavefront wg issues transfers wg, wg + 4, ..., wg + 16; transfer numbers past
-    // the tile's end go to a dump area.
+    // pieces re-read piece 0).  Wavefront wg issues the transfers wg, wg + 4, ... below the tile's transfer
+    // count (5 or 4 of them).
     const int row_bytes = grp ? K_ROW_BYTES : V_ROW_BYTES;
     const int n_xfer = grp ? K_TILE_BYTES / 1024 : V_TILE_BYTES / 1024;
+    // transfers this wavefront issues per tile: its share wg, wg + 4, ... of the tile's n_xfer (4 or 5)
+    const int my_xfers = (n_xfer - wg + 3) / 4;
     uint32_t fetch_off[DMA_PER_WAVE];   // byte offsets from the tile's first key
     int fetch_row[DMA_PER_WAVE];
 #pragma unroll
@@ -138,7 +139,6 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
         fetch_off[i] = 2u * (uint32_t)(r * (int)g.kv_stride_tok + c * 8);
     }
     const uint32_t lds_k = (uint32_t)(uintptr_t)(&sm.k[0][0]), lds_v = (uint32_t)(uintptr_t)(&sm.v[0][0]);
-    const uint32_t lds_dump = (uint32_t)(uintptr_t)(&sm.dump[0]);
     const uint16_t* fetch_src = grp ? k : v;                 // group 1 streams K, group 0 streams V
     const uint32_t fetch_lds = grp ? lds_k : lds_v;
     const int fetch_tile_bytes = grp ? K_TILE_BYTES : V_TILE_BYTES;
@@ -149,16 +149,14 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
         if (col0 + TN <= g.lc) {
 #pragma unroll
             for (int i = 0; i < DMA_PER_WAVE; ++i) {
-                const uint32_t d = wg + 4 * i < n_xfer ? dst + i * 4096 : lds_dump;
-                lds_dma16_base(src, fetch_off[i], __builtin_amdgcn_readfirstlane(d));
+                if (wg + 4 * i < n_xfer) lds_dma16_base(src, fetch_off[i], __builtin_amdgcn_readfirstlane(dst + i * 4096));
             }
         } else {   // ragged last tile: clamp the key index (the extra keys are masked through their position)
 #pragma unroll
             for (int i = 0; i < DMA_PER_WAVE; ++i) {
                 uint32_t off = fetch_off[i];
                 if (col0 + fetch_row[i] >= g.lc) off -= 2u * (uint32_t)((col0 + fetch_row[i] - (g.lc - 1)) * (int)g.kv_stride_tok);
-                const uint32_t d = wg + 4 * i < n_xfer ? dst + i * 4096 : lds_dump;
-                lds_dma16_base(src, off, __builtin_amdgcn_readfirstlane(d));
+                if (wg + 4 * i < n_xfer) lds_dma16_base(src, off, __builtin_amdgcn_readfirstlane(dst + i * 4096));
             }
         }
         // global positions of the tile's keys, for the tiles some row needs a mask for
@@ -319,18 +317,18 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
             for (int j = 0; j < n_pre && j < NT; ++j) fetch_tile(j);
         }
         if (grp == 1) {   // K(0) complete before anyone's M(0)
-            wait_tiles_in_flight((NT < K_AHEAD ? NT : K_AHEAD) - 1);
+            wait_tiles_in_flight((NT < K_AHEAD ? NT : K_AHEAD) - 1, my_xfers);
             wg_barrier();
         }
         // before M(t): group 0 has requested V up to min(t + 1, NT - 1) and needs V(t - 1) complete
         auto enter_m = [&](int t) __attribute__((always_inline)) {
-            if (grp == 0) wait_tiles_in_flight(NT - t < 2 ? NT - t : 2);
+            if (grp == 0) wait_tiles_in_flight(NT - t < 2 ? NT - t : 2, my_xfers);
             wg_barrier();
         };
         // before V(t): group 1 has requested K up to min(t + 3, NT - 1) and needs K(t + 1) complete; then the
         // vector phase itself, starting with this group's share of the fetches
         auto vector_part = [&](int t, auto first_c) __attribute__((always_inline)) {
-            if (grp == 1 && t + 1 < NT) wait_tiles_in_flight(NT - 2 - t < 2 ? NT - 2 - t : 2);
+            if (grp == 1 && t + 1 < NT) wait_tiles_in_flight(NT - 2 - t < 2 ? NT - 2 - t : 2, my_xfers);
             wg_barrier();
             const int j = t + (grp ? K_AHEAD : V_AHEAD);
             if (j < NT) fetch_tile(j);

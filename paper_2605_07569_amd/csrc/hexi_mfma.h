@@ -201,6 +201,16 @@ __device__ __forceinline__ void wait_tiles_in_flight(int allowed_tiles)
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
+// Same for a wavefront that issues `per_tile` (4 or 5, wave-uniform) transfers per tile.
+__device__ __forceinline__ void wait_tiles_in_flight(int allowed_tiles, int per_tile)
+{
+    if (per_tile == 5) wait_tiles_in_flight(allowed_tiles);
+    else if (allowed_tiles >= 3) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+    else if (allowed_tiles == 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else if (allowed_tiles == 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
 // Workgroup barrier that the compiler's scheduler does not move code across.
 __device__ __forceinline__ void wg_barrier()
 {
