@@ -108,6 +108,10 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
     const int NT = (seg_rows_le(g.ks, seg_pos_of_row(g.qs, wg_last_row)) + TN - 1) / TN;
     const int n_full_wg = seg_rows_le(g.ks, seg_pos_of_row(g.qs, row0)) / TN;
 
+    // A workgroup whose rows see nothing of the chunk leaves the running (o, lse) as they are: merging an empty
+    // partial is the identity.  (Without HEXI_ACCUMULATE it goes on and writes o = 0, lse = -inf.)
+    if (NT == 0 && a.accumulate) return;
+
     // Q^T operand fragments: lane (row l32, half hh) holds d = 16*ks + 8*hh .. +7
     bf16x8 qf[8];
     {
