@@ -14,11 +14,11 @@
 // and one issuing only VALU work.  Two wavefronts per SIMD leave 256 registers per wavefront, too few for
 // 32 keys x 128 columns of dK and dV (128 registers) next to the K / V fragments (64): the wavefronts of a
 // group therefore work in pairs on 32 keys.  Each of the two computes S, dP, P, dS for one 32-row half of
-// the q tile, publishes its P^T / dS^T operand fragments (bf16, 4 KB) in LDS, and accumulates dV and dK over
-// all 64 rows for one 64-column half of the head dimension: no product is computed twice, and the
-// accumulators shrink to 64 registers.
-//   M(i): dV += P^T dO, dK += dS^T Q of tile i-1 (16 MFMAs), then S and dP of tile i (16 MFMAs);
-//   V(i): P and dS of tile i, rounded to bf16 operand slots and written to the exchange area.
+// the q tile; then one of them accumulates dV and the other dK over all 64 rows, each taking its partner's
+// half of the operand it needs (P^T for dV, dS^T for dK; bf16 fragments, 2 KB per wavefront) from LDS.  No
+// product is computed twice, and the accumulators shrink to 64 registers.
+//   M(i): dV += P^T dO or dK += dS^T Q of tile i-1 (16 MFMAs), then S and dP of tile i (16 MFMAs);
+//   V(i): P and dS of tile i, rounded to bf16 operand slots; the partner's fragments go to the exchange area.
 // Q / dO tiles are triple-buffered in LDS (padded, row-permuted layout: conflict-free row and transposed reads
 // from single base registers) and fetched two tiles ahead with direct global->LDS loads: Q by group 1 at the
 // start of its vector phase, dO (+ LSE, Delta) by group 0 at the start of the matrix phase it runs in the
@@ -45,15 +45,15 @@ constexpr float LOG2E = 1.4426950408889634f;
 struct BwdSmem {
     unsigned char q[NB][P16_TILE_BYTES];   // 3 x 17 KB
     unsigned char g[NB][P16_TILE_BYTES];   // dO, 3 x 17 KB
-    unsigned char xch[8][4096];            // per wavefront: P^T fragments 0, 1 and dS^T fragments 0, 1 (64 lanes x 16 B each)
+    unsigned char xch[8][2048];            // per wavefront: the two fragments its partner needs (64 lanes x 16 B each)
     float lse[NB][TM];
     float delta[NB][TM];
     int qpos[8][TM];                       // row positions of the tiles that need a mask, written two tiles ahead
 };
 
-// LDS reads of matrix-phase step st: two transposed reads (+ one P^T / dS^T fragment on even steps) below 16,
-// one row read from 16 on
-__host__ __device__ constexpr int reads_of(int st) { return st < 16 ? 2 + ((st & 1) == 0 ? 1 : 0) : 1; }
+// LDS reads of matrix-phase step st: two transposed reads below 16 (+ a fragment of the partner's at steps 8
+// and 12), one row read from 16 on
+__host__ __device__ constexpr int reads_of(int st) { return st < 16 ? 2 + ((st == 8 || st == 12) ? 1 : 0) : 1; }
 
 // Runs of q heads: run r covers len[r] heads starting at first[r], linked through next[] (all read kv head
 // kv_of_q[first[r]]).
@@ -70,7 +70,7 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int grp = wave >> 2, wg4 = wave & 3, pair = wg4 >> 1, hd = wg4 & 1;
+    const int grp = wave >> 2, wg4 = wave & 3, pair = wg4 >> 1, role = wg4 & 1;   // role 0: dV, rows 0..31; 1: dK, rows 32..63
     const int l32 = lane & 31, hh = lane >> 5;
     const int grp2 = (lane >> 4) & 1, j16 = lane & 15;
 
@@ -117,12 +117,12 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) { pin(kf[ks]); pin(vf[ks]); }
     }
-    // dK / dV of this wavefront: 32 keys x columns [64*hd, 64*hd + 64), two 32-column blocks
-    f32x16 dk_acc[2], dv_acc[2];
+    // dV (role 0) or dK (role 1) of the pair's 32 keys: four 32-column blocks
+    f32x16 acc[4];
 #pragma unroll
-    for (int db = 0; db < 2; ++db)
+    for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { dk_acc[db][r] = 0.f; dv_acc[db][r] = 0.f; }
+        for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
     const float scale_log2 = g.scale * LOG2E;
 
     // Tile order within a head: first the tiles that need masking (the leading, partly visible q tiles and a
@@ -200,43 +200,43 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
 
     // Lane parts of the LDS byte addresses; buffer and step are compile-time offsets of the reads.
     //   row fragment ks of the wavefront's 32-row half, buffer B:   nat_addr[which] + B * TILE + 32 * ks
-    //   transposed fragment (16-row step kq, 32-column block db, half `second`) of buffer B: rows
-    //   16kq + 8*second + 4*hh + jj sit in LDS rows 16kq + 4*jj + 2*second + hh:
-    //        tr_addr[which] + B * TILE + (16 * kq + 2 * second) * ROW + 64 * db     (columns 64*hd + 32*db + ...)
-    //   P^T / dS^T fragment f of the pair's wavefront w':  xch_addr + w' * 4096 + f * 1024
-    // which = 0: dO tile, 1: Q tile for the transposed reads; 0: Q tile, 1: dO tile for the row reads.
+    //       (which = 0: Q tile for S, 1: dO tile for dP)
+    //   transposed fragment (16-row step kq of a 32-row half, 32-column block db, half `second`) of buffer B:
+    //   rows 16kq + 8*second + 4*hh + jj of the half sit in LDS rows 16kq + 4*jj + 2*second + hh of it:
+    //        tr_addr[half] + B * TILE + (16 * kq + 2 * second) * ROW + 64 * db
+    //       (the dO tile for the dV wavefront, the Q tile for the dK wavefront; half 0: its own rows, 1: its partner's)
+    //   the partner's fragment f:  xch_partner + f * 1024
     const int jj = j16 >> 2;
-    const uint32_t nat_lane = (32 * hd + p16_row(l32)) * P16_ROW_BYTES + 16 * hh;
-    const uint32_t tr_lane = (4 * jj + hh) * P16_ROW_BYTES + 2 * (16 * grp2 + 4 * (j16 & 3)) + 128 * hd;
+    const uint32_t nat_lane = (32 * role + p16_row(l32)) * P16_ROW_BYTES + 16 * hh;
+    const uint32_t tr_lane = (role ? lds_q : lds_g) + (4 * jj + hh) * P16_ROW_BYTES + 2 * (16 * grp2 + 4 * (j16 & 3));
     uint32_t nat_addr[2] = {lds_q + nat_lane, lds_g + nat_lane};
-    uint32_t tr_addr[2] = {lds_g + tr_lane, lds_q + tr_lane};
-    const uint32_t lds_xch = (uint32_t)(uintptr_t)(&sm.xch[0][0]);
-    const uint32_t xch_addr = lds_xch + (wave & ~1) * 4096 + lane * 16;
+    uint32_t tr_addr[2] = {tr_lane + 32 * role * P16_ROW_BYTES, tr_lane + 32 * (1 - role) * P16_ROW_BYTES};   // own rows, partner's rows
+    const uint32_t xch_partner = (uint32_t)(uintptr_t)(&sm.xch[wave ^ 1][0]) + lane * 16;
     bf16x8* xch_mine = reinterpret_cast<bf16x8*>(&sm.xch[wave][0]) + lane;
 
     f32x16 s, dp;
+    bf16x8 own[2];     // own operand fragments (P^T for the dV wavefront, dS^T for the dK wavefront)
 
-    // Matrix phase on buffers (B + NB - 1) % NB (previous tile) and B (this tile).  Steps 0..15: dV += P^T dO
-    // and dK += dS^T Q of the previous tile: 16-row step kq = st / 4 (rows 0..31 are wavefront hd = 0's, 32..63
-    // wavefront hd = 1's), product (st / 2) % 2, column block st % 2.  Steps 16..31: S and dP of this tile's
-    // 32-row half, alternating, ks = (st - 16) / 2.  [FIRST, LAST) selects the steps; operand fragments are
-    // requested PF steps ahead.
+    // Matrix phase on buffers (B + NB - 1) % NB (previous tile) and B (this tile).  Steps 0..15: this
+    // wavefront's product (dV += P^T dO or dK += dS^T Q) of the previous tile: steps 0..7 contract over its own
+    // 32 rows (fragments in registers), steps 8..15 over its partner's (fragments from LDS); 16-row step
+    // (st / 4) % 2, column block st % 4.  Steps 16..31: S and dP of this tile's 32-row half, alternating,
+    // ks = (st - 16) / 2.  [FIRST, LAST) selects the steps; operand fragments are requested PF steps ahead.
     auto m_phase = [&](auto bc, auto first_c, auto last_c) __attribute__((always_inline)) {
         constexpr int B = decltype(bc)::value, FIRST = decltype(first_c)::value, LAST = decltype(last_c)::value;
         constexpr int PF = 3, NS = PF + 1;   // a fragment's registers are busy from its request until its MFMA
         constexpr int BP = (B + NB - 1) % NB;
         s16x4 ta[NS], tb[NS];
         bf16x8 nb[NS];
-        bf16x8 af[3];                        // P^T / dS^T fragments: shared by the two column blocks of a step pair
+        bf16x8 pfr[2];                       // the partner's two fragments
         auto issue = [&](auto stc) __attribute__((always_inline)) {
             constexpr int st = decltype(stc)::value, slot = (st - FIRST) % NS;
             if constexpr (st < 16) {
-                constexpr int db = st & 1, which = (st >> 1) & 1, kq = st >> 2;
-                if constexpr (db == 0)
-                    lds_issue_b128<(kq >> 1) * 4096 + (2 * which + (kq & 1)) * 1024>(af[(st >> 1) % 3], xch_addr);
+                constexpr int half = st >> 3, kq = (st >> 2) & 1, db = st & 3;
+                if constexpr (st == 8 || st == 12) lds_issue_b128<kq * 1024>(pfr[kq], xch_partner);
                 constexpr int off = BP * P16_TILE_BYTES + 16 * kq * P16_ROW_BYTES + 64 * db;
-                lds_issue_tr16<off>(ta[slot], tr_addr[which]);
-                lds_issue_tr16<off + 2 * P16_ROW_BYTES>(tb[slot], tr_addr[which]);
+                lds_issue_tr16<off>(ta[slot], tr_addr[half]);
+                lds_issue_tr16<off + 2 * P16_ROW_BYTES>(tb[slot], tr_addr[half]);
             } else {
                 constexpr int which = (st - 16) & 1, ks = (st - 16) >> 1;
                 lds_issue_b128<B * P16_TILE_BYTES + 32 * ks>(nb[slot], nat_addr[which]);
@@ -245,19 +245,21 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
         auto step = [&](auto stc) __attribute__((always_inline)) {
             constexpr int st = decltype(stc)::value, slot = (st - FIRST) % NS;
             if constexpr (st + PF < LAST) issue(IC<st + PF>{});
-            // LDS reads younger than this step's fragments: those of the next PF steps that exist
             constexpr int hi = st + PF < LAST ? st + PF : LAST - 1;
             constexpr int younger = (hi >= st + 1 ? reads_of(st + 1) : 0) + (hi >= st + 2 ? reads_of(st + 2) : 0) +
                                     (hi >= st + 3 ? reads_of(st + 3) : 0);
             static_assert(PF == 3, "the sum above covers three steps");
             const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
             if constexpr (st < 16) {
-                constexpr int db = st & 1, which = (st >> 1) & 1;
-                // the wait ties all three registers: the P^T / dS^T fragment was requested before the transposed pair
-                asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(ta[slot]), "+v"(tb[slot]), "+v"(af[(st >> 1) % 3]) : "n"(younger));
-                const bf16x8 bfrag = join_halves(ta[slot], tb[slot]);
-                if constexpr (which == 0) dv_acc[db] = mfma32(af[(st >> 1) % 3], bfrag, dv_acc[db]);
-                else dk_acc[db] = mfma32(af[(st >> 1) % 3], bfrag, dk_acc[db]);
+                constexpr int half = st >> 3, kq = (st >> 2) & 1, db = st & 3;
+                if constexpr (half == 0) {
+                    lds_wait<younger>(ta[slot], tb[slot]);
+                    acc[db] = mfma32(own[kq], join_halves(ta[slot], tb[slot]), acc[db]);
+                } else {
+                    // the wait ties all three registers: the partner's fragment was requested before the transposed pair
+                    asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(ta[slot]), "+v"(tb[slot]), "+v"(pfr[kq]) : "n"(younger));
+                    acc[db] = mfma32(pfr[kq], join_halves(ta[slot], tb[slot]), acc[db]);
+                }
             } else {
                 constexpr int which = (st - 16) & 1, ks = (st - 16) >> 1;
                 lds_wait<younger>(nb[slot]);
@@ -272,13 +274,13 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
     };
 
     // Vector phase: P and dS of the wavefront's 32 rows x 32 keys.  Register x = 4*rb + t holds row
-    // 32*hd + 8*rb + 4*hh + t.  Rows whose LSE is -inf see nothing anywhere, so they only occur in masked tiles.
+    // 32*role + 8*rb + 4*hh + t.  Rows whose LSE is -inf see nothing anywhere, so they only occur in masked tiles.
     auto v_phase = [&](int buf, int qpos_slot, auto masked_c) __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked_c)::value;
         float p[16], ds[16];
 #pragma unroll
         for (int rb = 0; rb < 4; ++rb) {
-            const int r0 = 32 * hd + 8 * rb + 4 * hh;
+            const int r0 = 32 * role + 8 * rb + 4 * hh;
             const f32x4 l4 = *reinterpret_cast<const f32x4*>(&sm.lse[buf][r0]);
             const f32x4 d4 = *reinterpret_cast<const f32x4*>(&sm.delta[buf][r0]);
             int4 qp = make_int4(0, 0, 0, 0);
@@ -293,12 +295,15 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
                 ds[x] = pv * (dp[x] - d4[t]);
             }
         }
-        xch_mine[0 * 64] = pack_bf16x8(p[0], p[1], p[2], p[3], p[4], p[5], p[6], p[7]);
-        xch_mine[1 * 64] = pack_bf16x8(p[8], p[9], p[10], p[11], p[12], p[13], p[14], p[15]);
-        xch_mine[2 * 64] = pack_bf16x8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
-        xch_mine[3 * 64] = pack_bf16x8(ds[8], ds[9], ds[10], ds[11], ds[12], ds[13], ds[14], ds[15]);
+        const bf16x8 p0 = pack_bf16x8(p[0], p[1], p[2], p[3], p[4], p[5], p[6], p[7]);
+        const bf16x8 p1 = pack_bf16x8(p[8], p[9], p[10], p[11], p[12], p[13], p[14], p[15]);
+        const bf16x8 d0 = pack_bf16x8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
+        const bf16x8 d1 = pack_bf16x8(ds[8], ds[9], ds[10], ds[11], ds[12], ds[13], ds[14], ds[15]);
+        // the dV wavefront keeps P^T and hands dS^T to its partner; the dK wavefront the other way round
+        if (role == 0) { own[0] = p0; own[1] = p1; xch_mine[0] = d0; xch_mine[64] = d1; }
+        else { own[0] = d0; own[1] = d1; xch_mine[0] = p0; xch_mine[64] = p1; }
         // the fragments must be in LDS before the barrier that ends this phase
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(own[0]), "+v"(own[1]) :: "memory");
     };
 
     // Phase sequence of a group: M(0) V(0) M(1) V(1) ... M(n_seq), a barrier before every phase; group 1
@@ -351,23 +356,20 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
         if (grp == 0) wg_barrier();
     }
 
-    // dK / dV: lane holds column d = 64*hd + 32*db + l32; register r holds key wcol0 + 8*(r/4) + 4*hh + r%4
+    // dV (role 0) or dK (role 1): lane holds column d = 32*db + l32; register r holds key wcol0 + 8*(r/4) + 4*hh + r%4
+    float* out = role ? a.dk : a.dv;
+    const float out_scale = role ? g.scale : 1.0f;
 #pragma unroll
-    for (int db = 0; db < 2; ++db)
+    for (int db = 0; db < 4; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int col = wcol0 + 8 * (r >> 2) + 4 * hh + (r & 3);
             if (col < g.lc) {
-                const long long idx = ((long long)col * g.nkv + kvh) * D + 64 * hd + 32 * db + l32;
-                const float kk = dk_acc[db][r] * g.scale, vv = dv_acc[db][r];
-                if (ATOMIC_DKV) {
-                    global_atomic_add(a.dk + idx, kk);
-                    global_atomic_add(a.dv + idx, vv);
-                } else if (a.accumulate) {
-                    a.dk[idx] += kk; a.dv[idx] += vv;
-                } else {
-                    a.dk[idx] = kk; a.dv[idx] = vv;
-                }
+                const long long idx = ((long long)col * g.nkv + kvh) * D + 32 * db + l32;
+                const float val = acc[db][r] * out_scale;
+                if (ATOMIC_DKV) global_atomic_add(out + idx, val);
+                else if (a.accumulate) out[idx] += val;
+                else out[idx] = val;
             }
         }
 }
