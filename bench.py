@@ -147,9 +147,9 @@ def main():
 
 
 def hbm_bound_kernels(run, w, reps=10):
-    """The two elementwise steps of the path, outside the timed region: the Delta prepass (reads o fp32 and dO,
-    writes Delta) and the unfused two-term LSE merge (reads both partials, writes the accumulator), each
-    against the 8 TB/s HBM roof with its algorithmic bytes."""
+    """The HBM-bound steps, outside the timed region: the Delta prepass (reads o fp32 and dO, writes Delta), the
+    unfused two-term LSE merge (reads both partials, writes the accumulator) and the head redistribution that
+    precedes the all-to-all, each against the 8 TB/s HBM roof with its algorithmic bytes."""
     from paper_2605_07569_amd import hexi
     lq, nq, d = w.lq, w.n_q_heads, w.head_dim
     esz = 2 if w.dtype == "bf16" else 4
@@ -177,8 +177,24 @@ def hbm_bound_kernels(run, w, reps=10):
     delta_ms = timed(lambda: hexi.hexi_attn_bwd_chunk(desc1, w.q_segs, [(last_pos, 1)], run.q, k1, v1, run.o, run.d_o, run.lse,
                                                       run.delta, run.dq, dk1, dv1, flags=hexi.HEXI_COMPUTE_DELTA))
     delta_bytes = float(lq) * nq * (d * (4 + esz) + 4)   # read o (fp32) and dO, write Delta
-    res = {"merge_lse": {"ms": round(merge_ms, 4), "GB/s": round(merge_bytes / merge_ms / 1e6, 1),
-                         "frac_of_8TBps": round(merge_bytes / merge_ms / 1e6 / 8000.0, 3)}}
+    # head redistribution before the all-to-all (Sec. 3.2): the shard's fused Q|K|V tensor cut into the parts of
+    # three ranks with uneven head counts (half, a third and a sixth of the q heads, plus the kv heads they need)
+    nkv = w.n_kv_heads
+    fused = torch.empty((lq, nq + 2 * nkv, d), dtype=run.q.dtype, device=run.dev).normal_()
+    cuts = [0, nq // 2, nq // 2 + nq // 3, nq]
+    lists = []
+    for r in range(3):
+        heads = list(range(cuts[r], cuts[r + 1]))
+        kv = sorted({w.kv_of_q[h] if w.kv_of_q else h // (nq // nkv) for h in heads})
+        lists.append(heads + [nq + k for k in kv] + [nq + nkv + k for k in kv])
+    listed = sum(len(l) for l in lists)
+    packed = torch.empty((listed * lq * d,), dtype=run.q.dtype, device=run.dev)
+    pack_ms = timed(lambda: hexi.hexi_a2a_pack(fused, packed, lists))
+    a2a_bytes = 2.0 * listed * lq * d * esz              # every listed element read once and written once
+    res = {"a2a_pack": {"ms": round(pack_ms, 4), "GB/s": round(a2a_bytes / pack_ms / 1e6, 1),
+                        "frac_of_8TBps": round(a2a_bytes / pack_ms / 1e6 / 8000.0, 3), "MB_moved": round(a2a_bytes / 1e6, 1)}}
+    res.update({"merge_lse": {"ms": round(merge_ms, 4), "GB/s": round(merge_bytes / merge_ms / 1e6, 1),
+                         "frac_of_8TBps": round(merge_bytes / merge_ms / 1e6 / 8000.0, 3)}})
     if delta_ms > 0:
         res["delta"] = {"ms": round(delta_ms, 4), "GB/s": round(delta_bytes / delta_ms / 1e6, 1),
                         "frac_of_8TBps": round(delta_bytes / delta_ms / 1e6 / 8000.0, 3)}

@@ -147,6 +147,35 @@ int hexi_attn_bwd_chunk(const hexi_attn_desc* desc, const hexi_range* q_range, c
                         float* dq_acc, float* dk, float* dv, uint32_t flags,
                         void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Head redistribution either side of the ring (Sec. 3.2: heterogeneous all-to-all with per-rank split
+ * tables; sub-ring KV exchange, where non-contiguous head slices are packed into contiguous buffers
+ * before transfer; App. A.4: the part for rank j is s * n_j * d_h elements per tensor).
+ *
+ * x, y: DEVICE [s][n_heads_total][head_dim], elements of elem_bytes (2 or 4) bytes, d contiguous,
+ * heads packed, token stride x_stride_tok ELEMENTS (>= n_heads_total * head_dim).  This is a
+ * device's pre-A2A sequence shard with all heads, or any tensor a head subset is cut from (Q, K,
+ * V, or all three fused along the head axis).
+ * heads_per_rank: HOST int32[n_ranks], n_j >= 0.  head_list: HOST int32[sum n_j]: rank 0's heads,
+ * then rank 1's, ..., each in [0, n_heads_total), in the order the rank wants them; at most
+ * HEXI_A2A_MAX_SLOTS entries, n_ranks <= HEXI_A2A_MAX_RANKS.  Both are copied during the call.
+ * packed: DEVICE, contiguous: for j = 0 .. n_ranks-1 the part [s][n_j][head_dim] (sum n_j * s *
+ * head_dim elements in all).  hexi_a2a_pack gathers x into packed (a head may be listed for several
+ * ranks: replicated kv heads); hexi_a2a_unpack scatters packed into y, leaves heads that no rank
+ * lists untouched, and refuses a head listed twice (HEXI_EINVAL).  Results are exact copies.
+ * head_dim * elem_bytes and x_stride_tok * elem_bytes must be multiples of 16 and all base pointers
+ * 16-byte aligned (HEXI_EALIGN).  Enqueued on hip_stream, no synchronisation, nothing enqueued on
+ * error; s == 0 or an empty head_list is a no-op.
+ */
+#define HEXI_A2A_MAX_SLOTS 256
+#define HEXI_A2A_MAX_RANKS 64
+int hexi_a2a_pack(const void* x, void* packed, int64_t s, int32_t n_heads_total, int32_t head_dim, int32_t elem_bytes,
+                  int64_t x_stride_tok, int32_t n_ranks, const int32_t* heads_per_rank, const int32_t* head_list,
+                  void* hip_stream);
+int hexi_a2a_unpack(const void* packed, void* y, int64_t s, int32_t n_heads_total, int32_t head_dim, int32_t elem_bytes,
+                    int64_t y_stride_tok, int32_t n_ranks, const int32_t* heads_per_rank, const int32_t* head_list,
+                    void* hip_stream);
+
 /* Bytes of device workspace the chunk calls need for this descriptor and these lengths
  * (currently 0: no kernel uses scratch memory). */
 size_t hexi_workspace_bytes(const hexi_attn_desc* desc, int64_t lq, int64_t lc);

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhexi_attn.so")
-SOURCES = ["hexi_api.hip", "hexi_misc.hip", "hexi_f32.hip", "hexi_bf16_fwd.hip", "hexi_bf16_bwd.hip", "hexi_bf16_bwd_dq.hip"]
+SOURCES = ["hexi_api.hip", "hexi_misc.hip", "hexi_a2a.hip", "hexi_f32.hip", "hexi_bf16_fwd.hip", "hexi_bf16_bwd.hip", "hexi_bf16_bwd_dq.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-munsafe-fp-atomics", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-Wno-inline-asm",

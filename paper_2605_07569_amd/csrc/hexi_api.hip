@@ -3,6 +3,7 @@
 #include <cstdio>
 #include <cstring>
 #include <cmath>
+#include <vector>
 #include "hexi_internal.h"
 
 #define HEXI_EXPORT extern "C" __attribute__((visibility("default")))
@@ -222,4 +223,54 @@ HEXI_EXPORT int hexi_attn_bwd_chunk(const hexi_attn_desc* desc, const hexi_range
     }
     if (e != hipSuccess) return fail(HEXI_EHIP, "backward launch failed: %s", hipGetErrorString(e));
     return HEXI_OK;
+}
+
+static int a2a_call(bool pack, const void* x, void* packed, void* y, int64_t s, int32_t n_heads_total, int32_t head_dim,
+                    int32_t elem_bytes, int64_t stride_tok, int32_t n_ranks, const int32_t* heads_per_rank,
+                    const int32_t* head_list, void* hip_stream)
+{
+    if (s < 0 || n_heads_total < 1 || n_heads_total > 65535 || head_dim < 1) return fail(HEXI_EINVAL, "bad sizes s=%lld heads=%d d=%d", (long long)s, n_heads_total, head_dim);
+    if (elem_bytes != 2 && elem_bytes != 4) return fail(HEXI_EUNSUPPORTED, "elem_bytes %d", elem_bytes);
+    if (n_ranks < 0 || n_ranks > HEXI_A2A_MAX_RANKS || (n_ranks > 0 && !heads_per_rank)) return fail(HEXI_EINVAL, "bad n_ranks %d or null table", n_ranks);
+    const int64_t row_bytes = (int64_t)head_dim * elem_bytes;
+    if (stride_tok < (int64_t)n_heads_total * head_dim) return fail(HEXI_EINVAL, "token stride %lld smaller than a token", (long long)stride_tok);
+    if (row_bytes % 16 || (stride_tok * elem_bytes) % 16 || row_bytes > 65536) return fail(HEXI_EALIGN, "head_dim * elem_bytes and the token stride must be multiples of 16 bytes");
+    int n_slots = 0;
+    for (int j = 0; j < n_ranks; ++j) {
+        if (heads_per_rank[j] < 0) return fail(HEXI_EINVAL, "heads_per_rank[%d] negative", j);
+        n_slots += heads_per_rank[j];
+        if (n_slots > HEXI_A2A_MAX_SLOTS) return fail(HEXI_EUNSUPPORTED, "more than %d listed heads", HEXI_A2A_MAX_SLOTS);
+    }
+    if (n_slots > 0 && !head_list) return fail(HEXI_EINVAL, "null head_list");
+    std::vector<char> seen(pack ? 0 : n_heads_total, 0);
+    for (int i = 0; i < n_slots; ++i) {
+        if (head_list[i] < 0 || head_list[i] >= n_heads_total) return fail(HEXI_EINVAL, "head_list[%d] = %d out of range", i, head_list[i]);
+        if (!pack) {
+            if (seen[head_list[i]]) return fail(HEXI_EINVAL, "head %d listed twice in an unpack", head_list[i]);
+            seen[head_list[i]] = true;
+        }
+    }
+    if (s > 0 && n_slots > 0) {
+        const void* a = pack ? x : y;
+        if (!a || !packed) return fail(HEXI_EINVAL, "null tensor pointer");
+        if (!aligned16(a) || !aligned16(packed)) return fail(HEXI_EALIGN, "tensor base pointers must be 16-byte aligned");
+    }
+    hipError_t e = hexi_launch_a2a(pack, x, packed, y, s, n_heads_total, (int)row_bytes, stride_tok * elem_bytes, n_ranks,
+                                   heads_per_rank, head_list, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail(HEXI_EHIP, "a2a launch failed: %s", hipGetErrorString(e));
+    return HEXI_OK;
+}
+
+HEXI_EXPORT int hexi_a2a_pack(const void* x, void* packed, int64_t s, int32_t n_heads_total, int32_t head_dim, int32_t elem_bytes,
+                              int64_t x_stride_tok, int32_t n_ranks, const int32_t* heads_per_rank, const int32_t* head_list,
+                              void* hip_stream)
+{
+    return a2a_call(true, x, packed, nullptr, s, n_heads_total, head_dim, elem_bytes, x_stride_tok, n_ranks, heads_per_rank, head_list, hip_stream);
+}
+
+HEXI_EXPORT int hexi_a2a_unpack(const void* packed, void* y, int64_t s, int32_t n_heads_total, int32_t head_dim, int32_t elem_bytes,
+                                int64_t y_stride_tok, int32_t n_ranks, const int32_t* heads_per_rank, const int32_t* head_list,
+                                void* hip_stream)
+{
+    return a2a_call(false, nullptr, const_cast<void*>(packed), y, s, n_heads_total, head_dim, elem_bytes, y_stride_tok, n_ranks, heads_per_rank, head_list, hip_stream);
 }

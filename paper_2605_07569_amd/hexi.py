@@ -19,7 +19,7 @@ HEXI_TILE_EMPTY, HEXI_TILE_FULL, HEXI_TILE_PARTIAL = 0, 1, 2
 HEXI_MAX_SEGS = 16
 
 EXPORTS = ("hexi_shard_mask", "hexi_attn_fwd_chunk", "hexi_attn_merge_lse", "hexi_attn_bwd_chunk",
-           "hexi_workspace_bytes", "hexi_last_error", "hexi_version")
+           "hexi_a2a_pack", "hexi_a2a_unpack", "hexi_workspace_bytes", "hexi_last_error", "hexi_version")
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libhexi_attn.so")
@@ -68,6 +68,11 @@ def load():
     lib.hexi_attn_merge_lse.restype = ctypes.c_int
     lib.hexi_attn_bwd_chunk.argtypes = [dp, rp, rp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp, ctypes.c_size_t, vp]
     lib.hexi_attn_bwd_chunk.restype = ctypes.c_int
+    i32p = ctypes.POINTER(i32)
+    lib.hexi_a2a_pack.argtypes = [vp, vp, i64, i32, i32, i32, i64, i32, i32p, i32p, vp]
+    lib.hexi_a2a_pack.restype = ctypes.c_int
+    lib.hexi_a2a_unpack.argtypes = [vp, vp, i64, i32, i32, i32, i64, i32, i32p, i32p, vp]
+    lib.hexi_a2a_unpack.restype = ctypes.c_int
     lib.hexi_workspace_bytes.argtypes = [dp, i64, i64]
     lib.hexi_workspace_bytes.restype = ctypes.c_size_t
     lib.hexi_last_error.restype = ctypes.c_char_p
@@ -179,3 +184,27 @@ def hexi_attn_bwd_chunk(desc, q_segs, kv_segs, q, k, v, o, d_o, lse, delta, dq_a
 
 def hexi_workspace_bytes(desc, lq, lc):
     return int(load().hexi_workspace_bytes(ctypes.byref(desc), lq, lc))
+
+
+def _head_tables(head_lists):
+    counts = (ctypes.c_int32 * max(1, len(head_lists)))(*[len(h) for h in head_lists])
+    flat = [int(h) for heads in head_lists for h in heads]
+    heads = (ctypes.c_int32 * max(1, len(flat)))(*flat)
+    return counts, heads
+
+
+def hexi_a2a_pack(x, packed, head_lists, stream=None):
+    """x: [s, n_heads_total, d] (token stride may exceed a token); packed: contiguous 1-D buffer of the same
+    dtype with sum(len(l)) * s * d elements; head_lists: one list of head indices per destination rank."""
+    s, n, d = x.shape
+    counts, heads = _head_tables(head_lists)
+    _check(load().hexi_a2a_pack(_ptr(x), _ptr(packed), s, n, d, x.element_size(), x.stride(0), len(head_lists), counts, heads,
+                                _stream(stream)))
+
+
+def hexi_a2a_unpack(packed, y, head_lists, stream=None):
+    """Inverse of hexi_a2a_pack: scatters the per-rank parts of `packed` into y [s, n_heads_total, d]."""
+    s, n, d = y.shape
+    counts, heads = _head_tables(head_lists)
+    _check(load().hexi_a2a_unpack(_ptr(packed), _ptr(y), s, n, d, y.element_size(), y.stride(0), len(head_lists), counts, heads,
+                                  _stream(stream)))

@@ -18,7 +18,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "hexi_attn.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(hexi_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(hexi_[a-z0-9_]+)\s*\(", header))
     assert {"hexi_shard_mask", "hexi_attn_fwd_chunk", "hexi_attn_merge_lse", "hexi_attn_bwd_chunk"} <= declared
     lib = hexi.load()
     for name in declared:
@@ -140,3 +140,30 @@ def test_workload_geometry():
     x = wl.make_inputs(wl.config(1, shrink=8))
     y = wl.make_inputs(wl.config(1, shrink=8))
     assert all((x[n] == y[n]).all() for n in x) and x["q"].shape == (128, 4, 64)
+
+
+def test_a2a_argument_validation_without_gpu():
+    """hexi_a2a_pack / hexi_a2a_unpack check their tables on the host before anything is launched."""
+    lib = hexi.load()
+    i32 = ctypes.c_int32
+
+    def call(fn, s=4, n=6, d=128, eb=2, stride=None, counts=(2, 1), heads=(0, 5, 3), ptr=16, ranks=None):
+        stride = n * d if stride is None else stride
+        c = (i32 * max(1, len(counts)))(*counts)
+        h = (i32 * max(1, len(heads)))(*heads)
+        return fn(ctypes.c_void_p(ptr), ctypes.c_void_p(ptr), s, n, d, eb, stride, len(counts) if ranks is None else ranks, c, h, None)
+
+    for fn in (lib.hexi_a2a_pack, lib.hexi_a2a_unpack):
+        assert call(fn, s=0) == hexi.HEXI_OK                              # nothing to move: no launch
+        assert call(fn, counts=(), heads=()) == hexi.HEXI_OK
+        assert call(fn, heads=(0, 6, 3)) == hexi.HEXI_EINVAL              # head out of range
+        assert call(fn, heads=(0, -1, 3)) == hexi.HEXI_EINVAL
+        assert call(fn, counts=(2, -1)) == hexi.HEXI_EINVAL
+        assert call(fn, eb=3) == hexi.HEXI_EUNSUPPORTED
+        assert call(fn, d=12) == hexi.HEXI_EALIGN                         # 24-byte rows
+        assert call(fn, stride=6 * 128 - 8) == hexi.HEXI_EINVAL           # stride smaller than a token
+        assert call(fn, ptr=8) == hexi.HEXI_EALIGN
+        assert call(fn, ranks=65) == hexi.HEXI_EINVAL
+        assert call(fn, n=300, counts=(257,), heads=tuple(range(257))) == hexi.HEXI_EUNSUPPORTED
+    assert call(lib.hexi_a2a_unpack, heads=(0, 5, 0)) == hexi.HEXI_EINVAL  # a head written twice
+    assert b"twice" in lib.hexi_last_error()
