@@ -41,6 +41,7 @@ extern "C" {
 #define HEXI_EALIGN       (-3)  /* a tensor base pointer or token/head stride is not 16-byte aligned */
 #define HEXI_EWORKSPACE   (-4)  /* workspace smaller than hexi_workspace_bytes() */
 #define HEXI_EHIP         (-5)  /* the HIP runtime refused a launch */
+#define HEXI_EINFEASIBLE   (-6)  /* hexi_sched_solve: no candidate schedule fits the devices' memory */
 
 #define HEXI_BF16 0
 #define HEXI_F32  1
@@ -175,6 +176,66 @@ int hexi_a2a_pack(const void* x, void* packed, int64_t s, int32_t n_heads_total,
 int hexi_a2a_unpack(const void* packed, void* y, int64_t s, int32_t n_heads_total, int32_t head_dim, int32_t elem_bytes,
                     int64_t y_stride_tok, int32_t n_ranks, const int32_t* heads_per_rank, const int32_t* head_list,
                     void* hip_stream);
+
+/*
+ * Host-side performance model and hierarchical scheduler (Sec. 4: formalization, performance model,
+ * scheduler; App. A: cost and memory model; App. B: the scheduler's algorithm).  No GPU is touched.
+ * All pointers are HOST pointers; inputs are read during the call only.
+ *
+ * hexi_cluster: n_devices <= HEXI_SCHED_MAX_DEVICES; c[d] compute throughput (FLOP/s), b[d] memory
+ * bandwidth (bytes/s), m[d] HBM capacity and m_static[d] schedule-independent residency (bytes);
+ * alpha[i*n + j] startup latency (s) and bw[i*n + j] bandwidth (bytes/s) of the link i -> j (the
+ * diagonal is ignored).  hexi_model: L_tot, microbatch B, hidden size H, head dimension d_h, number of
+ * attention heads, bytes per element, activation-retention coefficient gamma_act (the paper uses 2).
+ * hexi_schedule: n_groups A2A groups forming a ring in index order; group_of[d] in [0, n_groups);
+ * l_group[k] = L_k (array of n_devices entries, the first n_groups used); s_pre[d], n_heads[d] per
+ * device, with sum_{d in G_k} s_pre = L_k, sum_{d in G_k} n_heads = number of heads for every group
+ * (every group attends with all heads over its block), sum_k L_k = L_tot.  Heads lie over a group's
+ * devices in device order.
+ *
+ * hexi_sched_cost: terms[0] = T_blk = terms[1] (max_d T_nonattn) + terms[2] (max_k T_A2A) + terms[3]
+ * (sum over the ring steps of T_step) in seconds (terms may be NULL); *is_feasible = 1 iff
+ * m_static + Mem_act <= m on every device.  A schedule that violates the constraints above is
+ * HEXI_EINVAL.
+ * hexi_sched_solve: the three-stage search (topology partitions incl. the Ring / Ulysses / USP
+ * layouts, group sequence splits, rank-level coordinate descent); writes the lowest-cost feasible
+ * schedule into *out (caller-allocated arrays of n_devices entries each; groups are numbered in
+ * order of their smallest device) and its T_blk into *cost.  opts may be NULL; zero fields take the
+ * defaults M1 = 64, M2 = 16, I_max = 100 (Sec. 4.3), gap_ratio = 4, token_quantum = 64, perturb =
+ * 1/32, move_tokens = max(1, L_tot / (quantum * n_devices * 16)) * quantum.  L_tot must be a multiple
+ * of the token quantum.  HEXI_EINFEASIBLE if nothing passes the memory filter.  Deterministic.
+ */
+#define HEXI_SCHED_MAX_DEVICES 4096
+typedef struct {
+    int32_t n_devices;
+    const double* c;
+    const double* b;
+    const double* m;
+    const double* m_static;
+    const double* alpha;
+    const double* bw;
+} hexi_cluster;
+typedef struct {
+    int64_t l_tot;
+    int32_t batch, hidden, head_dim, n_heads, dtype_bytes;
+    double gamma_act;
+} hexi_model;
+typedef struct {
+    int32_t m1, m2, i_max, token_quantum;
+    double gap_ratio, perturb;
+    int64_t move_tokens;
+} hexi_sched_opts;
+typedef struct {
+    int32_t n_groups;
+    int32_t* group_of;
+    int64_t* l_group;
+    int64_t* s_pre;
+    int32_t* n_heads;
+} hexi_schedule;
+int hexi_sched_cost(const hexi_cluster* cluster, const hexi_model* model, const hexi_schedule* schedule,
+                    double* terms, int32_t* is_feasible);
+int hexi_sched_solve(const hexi_cluster* cluster, const hexi_model* model, const hexi_sched_opts* opts,
+                     hexi_schedule* out, double* cost);
 
 /* Bytes of device workspace the chunk calls need for this descriptor and these lengths
  * (currently 0: no kernel uses scratch memory). */

@@ -260,7 +260,7 @@ def generate_candidates(cl, mo, groups, q, perturb):
     for g in groups:
         budget = min(cl.m[d] - cl.m_static[d] for d in g)
         per_token = mo.B * mo.P * (mo.gamma * mo.H / len(g) + 2.0 * (mo.N / len(g)) * mo.d_h)
-        cap.append(int(max(0.0, budget / per_token) // q) * q)
+        cap.append(int(math.floor(max(0.0, budget / per_token) / q)) * q)
     lens = largest_remainder(mo.l_tot, comp, q)
     for _ in range(K):
         over = [k for k in range(K) if lens[k] > cap[k]]

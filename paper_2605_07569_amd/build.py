@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhexi_attn.so")
-SOURCES = ["hexi_api.hip", "hexi_misc.hip", "hexi_a2a.hip", "hexi_f32.hip", "hexi_bf16_fwd.hip", "hexi_bf16_bwd.hip", "hexi_bf16_bwd_dq.hip"]
+SOURCES = ["hexi_api.hip", "hexi_sched.cpp", "hexi_misc.hip", "hexi_a2a.hip", "hexi_f32.hip", "hexi_bf16_fwd.hip", "hexi_bf16_bwd.hip", "hexi_bf16_bwd_dq.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-munsafe-fp-atomics", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-Wno-inline-asm",
@@ -22,8 +22,12 @@ def _hipcc():
 
 
 def _compile(src):
-    obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-    cmd = [_hipcc()] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+    obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
+    if src.endswith(".cpp"):   # host-only code: no device pass, no fused multiply-adds (results must not depend on them)
+        cmd = [_hipcc(), "-O2", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-ffp-contract=off",
+               "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-x", "c++", "-c", os.path.join(CSRC, src), "-o", obj]
+    else:
+        cmd = [_hipcc()] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:

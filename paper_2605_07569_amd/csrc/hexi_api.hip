@@ -19,6 +19,16 @@ static int fail(int code, const char* fmt, ...)
     return code;
 }
 
+// the same for the host-only translation units
+int hexi_set_error(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
 HEXI_EXPORT const char* hexi_last_error(void) { return g_err; }
 HEXI_EXPORT const char* hexi_version(void) { return "hexi-attn 0.1 (gfx950)"; }
 

@@ -12,14 +12,14 @@ from typing import List, Optional, Sequence, Tuple
 import numpy as np
 
 HEXI_OK = 0
-HEXI_EINVAL, HEXI_EUNSUPPORTED, HEXI_EALIGN, HEXI_EWORKSPACE, HEXI_EHIP = -1, -2, -3, -4, -5
+HEXI_EINVAL, HEXI_EUNSUPPORTED, HEXI_EALIGN, HEXI_EWORKSPACE, HEXI_EHIP, HEXI_EINFEASIBLE = -1, -2, -3, -4, -5, -6
 HEXI_BF16, HEXI_F32 = 0, 1
 HEXI_ACCUMULATE, HEXI_COMPUTE_DELTA, HEXI_SKIP_DQ, HEXI_SKIP_DKDV = 1, 2, 4, 8
 HEXI_TILE_EMPTY, HEXI_TILE_FULL, HEXI_TILE_PARTIAL = 0, 1, 2
 HEXI_MAX_SEGS = 16
 
 EXPORTS = ("hexi_shard_mask", "hexi_attn_fwd_chunk", "hexi_attn_merge_lse", "hexi_attn_bwd_chunk",
-           "hexi_a2a_pack", "hexi_a2a_unpack", "hexi_workspace_bytes", "hexi_last_error", "hexi_version")
+           "hexi_a2a_pack", "hexi_a2a_unpack", "hexi_sched_cost", "hexi_sched_solve", "hexi_workspace_bytes", "hexi_last_error", "hexi_version")
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libhexi_attn.so")
@@ -73,6 +73,10 @@ def load():
     lib.hexi_a2a_pack.restype = ctypes.c_int
     lib.hexi_a2a_unpack.argtypes = [vp, vp, i64, i32, i32, i32, i64, i32, i32p, i32p, vp]
     lib.hexi_a2a_unpack.restype = ctypes.c_int
+    lib.hexi_sched_cost.argtypes = [vp, vp, vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
+    lib.hexi_sched_cost.restype = ctypes.c_int
+    lib.hexi_sched_solve.argtypes = [vp, vp, vp, vp, ctypes.POINTER(ctypes.c_double)]
+    lib.hexi_sched_solve.restype = ctypes.c_int
     lib.hexi_workspace_bytes.argtypes = [dp, i64, i64]
     lib.hexi_workspace_bytes.restype = ctypes.c_size_t
     lib.hexi_last_error.restype = ctypes.c_char_p
@@ -208,3 +212,72 @@ def hexi_a2a_unpack(packed, y, head_lists, stream=None):
     counts, heads = _head_tables(head_lists)
     _check(load().hexi_a2a_unpack(_ptr(packed), _ptr(y), s, n, d, y.element_size(), y.stride(0), len(head_lists), counts, heads,
                                   _stream(stream)))
+
+
+class _Cluster(ctypes.Structure):
+    _fields_ = [("n_devices", ctypes.c_int32)] + [(k, ctypes.POINTER(ctypes.c_double)) for k in ("c", "b", "m", "m_static", "alpha", "bw")]
+
+
+class _Model(ctypes.Structure):
+    _fields_ = [("l_tot", ctypes.c_int64), ("batch", ctypes.c_int32), ("hidden", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("n_heads", ctypes.c_int32), ("dtype_bytes", ctypes.c_int32), ("gamma_act", ctypes.c_double)]
+
+
+class _SchedOpts(ctypes.Structure):
+    _fields_ = [("m1", ctypes.c_int32), ("m2", ctypes.c_int32), ("i_max", ctypes.c_int32), ("token_quantum", ctypes.c_int32),
+                ("gap_ratio", ctypes.c_double), ("perturb", ctypes.c_double), ("move_tokens", ctypes.c_int64)]
+
+
+class _Schedule(ctypes.Structure):
+    _fields_ = [("n_groups", ctypes.c_int32), ("group_of", ctypes.POINTER(ctypes.c_int32)), ("l_group", ctypes.POINTER(ctypes.c_int64)),
+                ("s_pre", ctypes.POINTER(ctypes.c_int64)), ("n_heads", ctypes.POINTER(ctypes.c_int32))]
+
+
+def _cluster_struct(c, b, m, m_static, alpha, bw):
+    n = len(c)
+    arrs = [np.ascontiguousarray(a, dtype=np.float64) for a in (c, b, m, m_static, np.asarray(alpha).reshape(-1), np.asarray(bw).reshape(-1))]
+    st = _Cluster(n, *[a.ctypes.data_as(ctypes.POINTER(ctypes.c_double)) for a in arrs])
+    return st, arrs
+
+
+def _model_struct(l_tot, batch, hidden, head_dim, n_heads, dtype_bytes, gamma_act=2.0):
+    return _Model(l_tot, batch, hidden, head_dim, n_heads, dtype_bytes, gamma_act)
+
+
+def hexi_sched_cost(cluster, model, groups, l_group, s_pre, n_heads):
+    """cluster: dict(c, b, m, m_static, alpha, bw); model: dict(l_tot, batch, hidden, head_dim, n_heads, dtype_bytes[, gamma_act]);
+    groups: list of device lists in ring order.  Returns (T_blk, max T_nonattn, max T_A2A, sum T_step, feasible)."""
+    cs, keep = _cluster_struct(**cluster)
+    ms = _model_struct(**model)
+    n = cs.n_devices
+    group_of = np.full(n, -1, dtype=np.int32)
+    for k, g in enumerate(groups):
+        for d in g:
+            group_of[d] = k
+    lg = np.zeros(n, dtype=np.int64)
+    lg[:len(groups)] = l_group
+    sp, nh = np.ascontiguousarray(s_pre, dtype=np.int64), np.ascontiguousarray(n_heads, dtype=np.int32)
+    sch = _Schedule(len(groups), group_of.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), lg.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                    sp.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), nh.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+    terms = (ctypes.c_double * 4)()
+    feas = ctypes.c_int32(0)
+    _check(load().hexi_sched_cost(ctypes.byref(cs), ctypes.byref(ms), ctypes.byref(sch), terms, ctypes.byref(feas)))
+    return terms[0], terms[1], terms[2], terms[3], bool(feas.value)
+
+
+def hexi_sched_solve(cluster, model, **opts):
+    """Returns dict(groups, l_group, s_pre, n_heads, cost).  opts: m1, m2, i_max, token_quantum, gap_ratio, perturb, move_tokens."""
+    cs, keep = _cluster_struct(**cluster)
+    ms = _model_struct(**model)
+    n = cs.n_devices
+    o = _SchedOpts(opts.get("m1", 0), opts.get("m2", 0), opts.get("i_max", 0), opts.get("token_quantum", 0),
+                   opts.get("gap_ratio", 0.0), opts.get("perturb", 0.0), opts.get("move_tokens", 0))
+    group_of, lg = np.zeros(n, dtype=np.int32), np.zeros(n, dtype=np.int64)
+    sp, nh = np.zeros(n, dtype=np.int64), np.zeros(n, dtype=np.int32)
+    sch = _Schedule(0, group_of.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), lg.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                    sp.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), nh.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+    cost = ctypes.c_double(0.0)
+    _check(load().hexi_sched_solve(ctypes.byref(cs), ctypes.byref(ms), ctypes.byref(o), ctypes.byref(sch), ctypes.byref(cost)))
+    groups = [[d for d in range(n) if group_of[d] == k] for k in range(sch.n_groups)]
+    return dict(groups=groups, l_group=[int(x) for x in lg[:sch.n_groups]], s_pre=[int(x) for x in sp], n_heads=[int(x) for x in nh],
+                cost=cost.value)
