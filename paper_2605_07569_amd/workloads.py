@@ -106,6 +106,23 @@ def config(idx: int, seed: int = 20260507, shrink: int = 1) -> Workload:
     return w
 
 
+def from_schedule(groups, l_group, n_heads, device: int, head_dim: int = 128, q_per_kv: int = 1, dtype: str = "bf16") -> Workload:
+    """The attention share a schedule gives one device (Sec. 4.1: A2A groups in ring order, group sequence
+    lengths L_k, per-rank head counts n_d): group k holds the sequence block [sum_{k'<k} L_k', + L_k) after the
+    all-to-all, the device holds its contiguous range of n_d q heads (heads lie over a group's devices in device
+    order), and the ring delivers the blocks of groups k, k-1, ... (mod K).  With GQA (q_per_kv q heads per kv
+    head) the range may cut through a kv group: the kv heads it touches are held locally and kv_of_q maps onto them."""
+    k = next(i for i, g in enumerate(groups) if device in g)
+    starts = [sum(l_group[:i]) for i in range(len(groups))]
+    lo = sum(n_heads[d] for d in groups[k] if d < device)
+    q_heads = list(range(lo, lo + n_heads[device]))
+    kv_global = sorted({h // q_per_kv for h in q_heads})
+    kv_of_q = [kv_global.index(h // q_per_kv) for h in q_heads]
+    chunks = [[(starts[(k - t) % len(groups)], l_group[(k - t) % len(groups)])] for t in range(len(groups))]
+    return Workload(f"sched_dev{device}", dtype, len(q_heads), len(kv_global), head_dim, sum(l_group), [(starts[k], l_group[k])], chunks,
+                    kv_of_q=kv_of_q, note=f"device {device} of a scheduled plan: group {k} of {len(groups)}, q heads {lo}..{lo + len(q_heads) - 1}")
+
+
 def contiguous_chunks(w: Workload, n_chunks: int) -> Workload:
     """Alternative chunking of the same key set: n equal contiguous chunks at offsets j*Lc."""
     lc = w.l_tot // n_chunks

@@ -288,3 +288,21 @@ def test_forward_exact_softmax_fallback():
         check("o", o.cpu(), o_ref, "bf16")
         # lse values reach the hundreds here: the absolute bound scales with them (fp32 has 24 bits)
         check("lse", lse.cpu(), lse_ref, "bf16", abs_factor=max(1.0, float(np.max(np.abs(lse_ref))) * 1e-2))
+
+
+def test_device_share_of_a_scheduled_plan():
+    # host scheduler -> shard descriptor -> attention kernels: with 3 heads on two fast + two slow devices the
+    # plan is two node groups of uneven length with uneven head counts; one device per group runs its share
+    # (its group's block, its head range, which cuts through a GQA group; the ring's blocks in order, the
+    # later group's block lying in the first group's future) against the oracle
+    import sys, os
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+    from sched_util import cluster_arrays, model_args
+    arr = cluster_arrays([("h100", 2), ("a800", 2)])
+    plan = hexi.hexi_sched_solve(arr, model_args(l_tot=4096, n_heads=3, hidden=384), token_quantum=64, m2=4, i_max=20)
+    print("\nplan:", plan)
+    assert plan["groups"] == [[0, 1], [2, 3]] and sum(plan["l_group"]) == 4096 and plan["l_group"][0] != plan["l_group"][1]
+    for dev in (1, 2):
+        w = wl.from_schedule(plan["groups"], plan["l_group"], plan["n_heads"], dev, head_dim=128, q_per_kv=2)
+        assert w.n_q_heads == plan["n_heads"][dev] and len(w.chunks) == 2
+        _run_and_compare(w, seed=31 + dev)
