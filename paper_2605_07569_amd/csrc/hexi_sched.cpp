@@ -3,6 +3,8 @@
 // searches the schedule space in three stages.  No device code; double precision, every formula evaluated in
 // the order the paper writes it.  Readings of what the paper leaves open are stated at each function.
 #include <algorithm>
+#include <atomic>
+#include <thread>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -425,8 +427,8 @@ HEXI_EXPORT int hexi_sched_solve(const hexi_cluster* cluster, const hexi_model* 
     const long long q = opts && opts->token_quantum > 0 ? opts->token_quantum : 64;
     if (mo.l_tot % q) return hexi_set_error(HEXI_EINVAL, "L_tot = %lld is not a multiple of the token quantum %lld", mo.l_tot, q);
     const long long move_tokens = opts && opts->move_tokens > 0 ? opts->move_tokens : std::max(1LL, mo.l_tot / (q * cl.n * 16)) * q;
-    Sched best;
-    double best_c = INF;
+    // Stages I and II: the shortlist of (partition, group plan) starting points, in a fixed order
+    std::vector<Sched> starts;
     for (const Partition& groups : partition_topology(cl, m1, gap_ratio)) {
         struct Scored { double cost; int idx; Sched T; };
         std::vector<Scored> scored;
@@ -436,12 +438,28 @@ HEXI_EXPORT int hexi_sched_solve(const hexi_cluster* cluster, const hexi_model* 
             if (feasible(cl, mo, T)) scored.push_back({t_blk(cl, mo, T), i, T});
         }
         std::sort(scored.begin(), scored.end(), [](const Scored& x, const Scored& y) { return x.cost != y.cost ? x.cost < y.cost : x.idx < y.idx; });
-        for (int i = 0; i < (int)scored.size() && i < m2; ++i) {
-            Sched T = scored[i].T;
-            const double C = refine(cl, mo, T, i_max, move_tokens);
-            if (C < best_c) { best = T; best_c = C; }
-        }
+        for (int i = 0; i < (int)scored.size() && i < m2; ++i) starts.push_back(scored[i].T);
     }
+    // Stage III: the descents are independent of each other, so they run on the host's cores; the winner is
+    // picked afterwards in shortlist order (first strictly smaller cost), so the result does not depend on timing
+    std::vector<double> costs(starts.size(), INF);
+    {
+        std::atomic<size_t> next{0};
+        auto worker = [&]() {
+            for (size_t i = next.fetch_add(1); i < starts.size(); i = next.fetch_add(1)) costs[i] = refine(cl, mo, starts[i], i_max, move_tokens);
+        };
+        unsigned n_threads = std::thread::hardware_concurrency();
+        n_threads = n_threads == 0 ? 1 : (n_threads > 16 ? 16 : n_threads);
+        if (n_threads > starts.size()) n_threads = (unsigned)starts.size();
+        std::vector<std::thread> pool;
+        for (unsigned t = 1; t < n_threads; ++t) pool.emplace_back(worker);
+        worker();
+        for (auto& th : pool) th.join();
+    }
+    Sched best;
+    double best_c = INF;
+    for (size_t i = 0; i < starts.size(); ++i)
+        if (costs[i] < best_c) { best = starts[i]; best_c = costs[i]; }
     if (best_c == INF) return hexi_set_error(HEXI_EINFEASIBLE, "no candidate schedule passes the memory filter");
     out->n_groups = (int)best.groups.size();
     for (int k = 0; k < out->n_groups; ++k) {
