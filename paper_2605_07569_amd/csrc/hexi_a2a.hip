@@ -6,6 +6,8 @@
 
 namespace {
 
+typedef unsigned int u4 __attribute__((ext_vector_type(4)));   // one 16-byte piece
+
 // One slot per (rank, head of that rank's list), in send-buffer order.
 struct A2ATable {
     int n_slots;
@@ -24,7 +26,7 @@ constexpr int TOKENS_PER_BLOCK = 16;
 // a row, then consecutive slots, so both sides are accessed in runs of whole rows (the packed side in runs of a
 // whole rank's heads).
 template <bool PACK>
-__global__ void __launch_bounds__(256) a2a_kernel(const A2ATable tb, const uint4* __restrict__ x, uint4* __restrict__ packed, uint4* __restrict__ y,
+__global__ void __launch_bounds__(256) a2a_kernel(const A2ATable tb, const u4* __restrict__ x, u4* __restrict__ packed, u4* __restrict__ y,
                                                   const long long s, const int cpr, const long long x_stride_pieces)
 {
     const long long t0 = (long long)blockIdx.x * TOKENS_PER_BLOCK;
@@ -38,15 +40,15 @@ __global__ void __launch_bounds__(256) a2a_kernel(const A2ATable tb, const uint4
         long long in_p = (((long long)tb.heads_before[slot] * s + t0 * n_j) + tb.local[slot]) * cpr + c;
         const long long step_p = n_j * cpr;
         for (int tl = 0; tl < n_tok; tl += UNROLL) {
-            uint4 val[UNROLL];
+            u4 val[UNROLL];
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u)
-                if (tl + u < n_tok) val[u] = PACK ? x[in_x + u * x_stride_pieces] : packed[in_p + u * step_p];
+                if (tl + u < n_tok) val[u] = __builtin_nontemporal_load(PACK ? &x[in_x + u * x_stride_pieces] : &packed[in_p + u * step_p]);
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u)
                 if (tl + u < n_tok) {
-                    if (PACK) packed[in_p + u * step_p] = val[u];
-                    else y[in_x + u * x_stride_pieces] = val[u];
+                    if (PACK) __builtin_nontemporal_store(val[u], &packed[in_p + u * step_p]);
+                    else __builtin_nontemporal_store(val[u], &y[in_x + u * x_stride_pieces]);
                 }
             in_x += UNROLL * x_stride_pieces;
             in_p += UNROLL * step_p;
@@ -74,10 +76,10 @@ hipError_t hexi_launch_a2a(bool pack, const void* x, void* packed, void* y, long
     if (slot == 0 || s == 0) return hipSuccess;
     const unsigned grid = (unsigned)((s + TOKENS_PER_BLOCK - 1) / TOKENS_PER_BLOCK);
     if (pack)
-        a2a_kernel<true><<<grid, 256, 0, st>>>(tb, static_cast<const uint4*>(x), static_cast<uint4*>(packed), nullptr, s, row_bytes / 16,
+        a2a_kernel<true><<<grid, 256, 0, st>>>(tb, static_cast<const u4*>(x), static_cast<u4*>(packed), nullptr, s, row_bytes / 16,
                                                x_stride_bytes / 16);
     else
-        a2a_kernel<false><<<grid, 256, 0, st>>>(tb, nullptr, static_cast<uint4*>(packed), static_cast<uint4*>(y), s, row_bytes / 16,
+        a2a_kernel<false><<<grid, 256, 0, st>>>(tb, nullptr, static_cast<u4*>(packed), static_cast<u4*>(y), s, row_bytes / 16,
                                                 x_stride_bytes / 16);
     return hipGetLastError();
 }
