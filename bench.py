@@ -19,7 +19,7 @@ import torch
 PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16 MFMA peak: 256 CU x 2.4 GHz x 4096 flop/clk/CU
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # command (see profiles/); None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {"cfg2_3b_zigzag": 0.650e9}   # bwd_dkdv_bf16_kernel<false>: 486 MB fetched + 164 MB written
+MEASURED_TRAFFIC_BYTES = {"cfg2_3b_zigzag": 0.676e9}   # bwd_dkdv_bf16_kernel<false>: 496 MB fetched + 180 MB written
 
 
 def parse():
