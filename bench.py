@@ -32,6 +32,7 @@ def parse():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a kernel of known HBM traffic) before the timed "
                          "region, to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings")
+    ap.add_argument("--no-mfma-probe", action="store_true", help="skip the register-only MFMA rate measurement")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows per q segment for the oracle sample (0: auto)")
     return ap.parse_args()
 
@@ -140,10 +141,40 @@ def main():
                                "tflops": round(paper_flops / (ms_per_step * 1e-3) / 1e12, 2),
                                "note": "16*Lq*Lc*nq*d per live ring step (App. A.4 Eq. 11), masked pairs included"}
     out["hbm_bound_kernels"] = hbm_bound_kernels(run, w)
+    if is_bf16 and not args.no_mfma_probe:
+        out["mfma_probe"] = mfma_probe()
+        # context only: frac stays against the nominal peak
+        out["roofline"]["frac_of_measured_mfma_rate"] = round(achieved / out["mfma_probe"]["random_tflops"], 4)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, inputs, args.cpu_rows, n_pairs)
     print(json.dumps(out), flush=True)
+
+
+def mfma_probe(seconds=1.0, iters=100000):
+    """What the matrix cores sustain with nothing else going on: a register-only MFMA loop on zero and on
+    random bf16 operands, each run for about `seconds` (the clock needs some tenths of a second to settle
+    under the load) and timed over its last launches.  Context for `roofline.frac`: the nominal peak assumes 2.4 GHz."""
+    from paper_2605_07569_amd import hexi
+    dev = torch.device("cuda:0")
+    sink = torch.empty(256 * 512, dtype=torch.float32, device=dev)
+    flops = 256.0 * 8 * 4 * iters * 32768
+    res = {}
+    for name, ops in (("zeros", torch.zeros(32768, dtype=torch.bfloat16, device=dev)),
+                      ("random", torch.empty(32768, dtype=torch.float32, device=dev).uniform_(-2.5, 2.5).to(torch.bfloat16))):
+        t_end = time.perf_counter() + seconds
+        ms = []
+        while time.perf_counter() < t_end:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            hexi.hexi_mfma_probe(ops, sink, iters)
+            e1.record()
+            torch.cuda.synchronize()
+            ms.append(e0.elapsed_time(e1))
+        tail = ms[-max(1, len(ms) // 4):]
+        res[name + "_tflops"] = round(flops / (sum(tail) / len(tail) * 1e-3) / 1e12, 1)
+    res["note"] = "register-only v_mfma_f32_32x32x16_bf16 loop, whole chip; the shader clock is power-limited and depends on the operand bits"
+    return res
 
 
 def hbm_bound_kernels(run, w, reps=10):

@@ -237,6 +237,15 @@ int hexi_sched_cost(const hexi_cluster* cluster, const hexi_model* model, const 
 int hexi_sched_solve(const hexi_cluster* cluster, const hexi_model* model, const hexi_sched_opts* opts,
                      hexi_schedule* out, double* cost);
 
+/*
+ * Measurement aid: a register-only loop of v_mfma_f32_32x32x16_bf16 on the whole chip (256 workgroups
+ * x 8 wavefronts x 4 x iters MFMAs of 32768 flop), for the MFMA rate the part sustains on given
+ * operand bits (the shader clock is power-limited and depends on them).  operands: DEVICE, 65536
+ * bytes of bf16 values, 16-byte aligned; sink: DEVICE float[256 * 512], overwritten.  Enqueued on
+ * hip_stream; the caller times it.
+ */
+int hexi_mfma_probe(const void* operands, float* sink, int32_t iters, void* hip_stream);
+
 /* Bytes of device workspace the chunk calls need for this descriptor and these lengths
  * (currently 0: no kernel uses scratch memory). */
 size_t hexi_workspace_bytes(const hexi_attn_desc* desc, int64_t lq, int64_t lc);

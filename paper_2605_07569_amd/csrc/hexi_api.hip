@@ -284,3 +284,13 @@ HEXI_EXPORT int hexi_a2a_unpack(const void* packed, void* y, int64_t s, int32_t 
 {
     return a2a_call(false, nullptr, const_cast<void*>(packed), y, s, n_heads_total, head_dim, elem_bytes, y_stride_tok, n_ranks, heads_per_rank, head_list, hip_stream);
 }
+
+HEXI_EXPORT int hexi_mfma_probe(const void* operands, float* sink, int32_t iters, void* hip_stream)
+{
+    if (!operands || !sink || iters < 1) return fail(HEXI_EINVAL, "null pointer or iters < 1");
+    if (!aligned16(operands)) return fail(HEXI_EALIGN, "operands must be 16-byte aligned");
+    hipError_t e = hexi_launch_mfma_probe(operands, sink, iters, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail(HEXI_EHIP, "probe launch failed: %s", hipGetErrorString(e));
+    return HEXI_OK;
+}
+

@@ -73,6 +73,7 @@ hipError_t hexi_launch_merge(long long n_rows, int nq, int d, float* o_acc, floa
 hipError_t hexi_launch_delta(long long lq, int nq, int d, const float* o, const void* d_o, int dtype,
                              long long stride_tok, long long stride_head, float* delta, hipStream_t s);
 hipError_t hexi_launch_fill_f32(float* p, long long n, float value, hipStream_t s);
+hipError_t hexi_launch_mfma_probe(const void* operands, float* sink, int iters, hipStream_t s);
 // pack (x -> packed) or unpack (packed -> y, which has x's layout); host tables, validated by the caller
 hipError_t hexi_launch_a2a(bool pack, const void* x, void* packed, void* y, long long s, int n_heads_total, int row_bytes,
                            long long x_stride_bytes, int n_ranks, const int* heads_per_rank, const int* head_list, hipStream_t st);

@@ -19,7 +19,7 @@ HEXI_TILE_EMPTY, HEXI_TILE_FULL, HEXI_TILE_PARTIAL = 0, 1, 2
 HEXI_MAX_SEGS = 16
 
 EXPORTS = ("hexi_shard_mask", "hexi_attn_fwd_chunk", "hexi_attn_merge_lse", "hexi_attn_bwd_chunk",
-           "hexi_a2a_pack", "hexi_a2a_unpack", "hexi_sched_cost", "hexi_sched_solve", "hexi_workspace_bytes", "hexi_last_error", "hexi_version")
+           "hexi_a2a_pack", "hexi_a2a_unpack", "hexi_sched_cost", "hexi_sched_solve", "hexi_mfma_probe", "hexi_workspace_bytes", "hexi_last_error", "hexi_version")
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libhexi_attn.so")
@@ -77,6 +77,8 @@ def load():
     lib.hexi_sched_cost.restype = ctypes.c_int
     lib.hexi_sched_solve.argtypes = [vp, vp, vp, vp, ctypes.POINTER(ctypes.c_double)]
     lib.hexi_sched_solve.restype = ctypes.c_int
+    lib.hexi_mfma_probe.argtypes = [vp, vp, i32, vp]
+    lib.hexi_mfma_probe.restype = ctypes.c_int
     lib.hexi_workspace_bytes.argtypes = [dp, i64, i64]
     lib.hexi_workspace_bytes.restype = ctypes.c_size_t
     lib.hexi_last_error.restype = ctypes.c_char_p
@@ -281,3 +283,9 @@ def hexi_sched_solve(cluster, model, **opts):
     groups = [[d for d in range(n) if group_of[d] == k] for k in range(sch.n_groups)]
     return dict(groups=groups, l_group=[int(x) for x in lg[:sch.n_groups]], s_pre=[int(x) for x in sp], n_heads=[int(x) for x in nh],
                 cost=cost.value)
+
+
+def hexi_mfma_probe(operands, sink, iters, stream=None):
+    """operands: 65536 bytes of bf16 on the device; sink: float32[256 * 512] on the device."""
+    _check(load().hexi_mfma_probe(_ptr(operands), _ptr(sink), int(iters), _stream(stream)))
+
