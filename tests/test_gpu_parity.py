@@ -127,6 +127,38 @@ def test_dkdv_head_runs(run_len, monkeypatch):
     _run_and_compare(w, seed=22, fused=False)
 
 
+def _random_case(rng, i):
+    """A seeded random shard: the sequence [0, L) cut into pieces, each piece dealt to one of 1-4 chunks, the q
+    shard takes 1-3 pieces; random head counts and kv map."""
+    dtype = "bf16" if i % 3 else "f32"
+    d = 128 if dtype == "bf16" else int(rng.choice([64, 128]))
+    L = int(rng.integers(200, 1400))
+    n_pieces = int(rng.integers(2, 9))
+    cuts = sorted(set(int(c) for c in rng.integers(1, L, size=n_pieces - 1)))
+    edges = [0] + cuts + [L]
+    pieces = [(a, b - a) for a, b in zip(edges[:-1], edges[1:])]
+    # every piece goes to exactly one chunk (the chunks together hold every key the shard can see); a chunk's
+    # pieces need not be adjacent, so its segment list has holes, as a zigzag pair does
+    n_chunks = int(rng.integers(1, min(4, len(pieces)) + 1))
+    owner = rng.integers(0, n_chunks, size=len(pieces))
+    chunks = [[p for p, o in zip(pieces, owner) if o == c] for c in range(n_chunks)]
+    chunks = [c for c in chunks if c]
+    rng.shuffle(chunks)                       # the ring may deliver them in any order
+    own = sorted(rng.choice(len(pieces), size=min(len(pieces), int(rng.integers(1, 4))), replace=False).tolist())
+    q_segs = [pieces[k] for k in own]
+    nkv = int(rng.integers(1, 4))
+    nq = int(rng.integers(nkv, 9))
+    kv_of_q = sorted(int(x) for x in rng.integers(0, nkv, size=nq)) if rng.random() < 0.5 else [int(x) for x in rng.integers(0, nkv, size=nq)]
+    return _custom(f"rand{i}_{dtype}", dtype, nq, nkv, d, L, q_segs, chunks, kv_of_q=kv_of_q)
+
+
+def test_randomized_small_shards():
+    rng = np.random.default_rng(20260507)
+    for i in range(16):
+        w = _random_case(rng, i)
+        _run_and_compare(w, seed=100 + i, fused=bool(i % 2))
+
+
 def test_strided_inputs_and_accumulate_flags():
     # q/dO and k/v are slices of wider buffers (token and head strides larger than dense)
     w = _custom("strided", "bf16", 4, 2, 128, 512, [(128, 384)], [[(0, 256)], [(256, 256)]])
