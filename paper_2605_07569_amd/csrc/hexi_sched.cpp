@@ -319,39 +319,117 @@ std::vector<GroupPlan> generate_candidates(const Cluster& cl, const Model& mo, c
     return out;
 }
 
+// Ring cost of group k at step t: the slowest of its devices (the inner part of T_step, per group).
+double group_step(const Cluster& cl, const Model& mo, const Sched& T, int t, int k)
+{
+    const int K = (int)T.groups.size();
+    const int src = ((k - t) % K + K) % K, pred = ((k - 1) % K + K) % K;
+    double worst = 0.0;
+    int lo = 0;
+    for (int d : T.groups[k]) {
+        const int hi = lo + T.n_heads[d];
+        const double flops = 16.0 * (double)mo.B * (double)T.l_group[k] * (double)T.l_group[src] * (double)((long long)T.n_heads[d] * mo.d_h);
+        double cost = flops / cl.c[d];
+        if (t > 0 && T.n_heads[d] > 0) {
+            const double msg = 4.0 * (double)mo.B * (double)T.l_group[src] * (double)((long long)T.n_heads[d] * mo.d_h) * (double)mo.P;
+            double comm = 0.0;
+            int ulo = 0;
+            for (int u : T.groups[pred]) {
+                const int uhi = ulo + T.n_heads[u];
+                const int ov = std::min(hi, uhi) - std::max(lo, ulo);
+                if (ov > 0) comm = std::max(comm, cl.al(u, d) + (msg * (double)ov / (double)T.n_heads[d]) / cl.w(u, d));
+                ulo = uhi;
+            }
+            cost = std::max(cost, comm);
+        }
+        worst = std::max(worst, cost);
+        lo = hi;
+    }
+    return worst;
+}
+
 // Coordinate descent of Stage III: ordered pairs of distinct devices in the same or ring-adjacent groups,
 // lexicographic; per pair first `move_tokens` tokens from a to b (the group lengths follow when the groups
 // differ), then one head from a to b (same group only); the first strictly improving feasible move is taken.
+// The model's terms are kept per device (T_nonattn), per group (T_A2A) and per (step, group) (ring cost), and a
+// proposal recomputes only the entries its move touches: a token move inside a group changes two devices'
+// T_nonattn and the group's T_A2A; one between groups also the ring cost of every (step, group) whose query or
+// source block is one of the two; a head move the group's T_A2A, its own ring costs and its ring successor's
+// (whose senders' head ranges moved).  The terms are combined exactly as in t_blk, so the values are the same.
 double refine(const Cluster& cl, const Model& mo, Sched& T, int i_max, long long move_tokens)
 {
-    const int K = (int)T.groups.size();
-    std::vector<int> group_of(cl.n);
+    const int K = (int)T.groups.size(), n = cl.n;
+    std::vector<int> group_of(n);
     for (int k = 0; k < K; ++k) for (int d : T.groups[k]) group_of[d] = k;
-    double C = t_blk(cl, mo, T);
+    std::vector<double> na(n), a2a(K), ring((size_t)K * K), na2, a2a2, ring2;
+    for (int d = 0; d < n; ++d) na[d] = t_nonattn(cl, mo, T, d);
+    for (int k = 0; k < K; ++k) a2a[k] = t_a2a(cl, mo, T, k);
+    for (int t = 0; t < K; ++t) for (int k = 0; k < K; ++k) ring[(size_t)t * K + k] = group_step(cl, mo, T, t, k);
+    auto total = [&](const std::vector<double>& v_na, const std::vector<double>& v_a2a, const std::vector<double>& v_ring) {
+        double a = v_na[0], b = v_a2a[0], c = 0.0;
+        for (int d = 1; d < n; ++d) a = std::max(a, v_na[d]);
+        for (int k = 1; k < K; ++k) b = std::max(b, v_a2a[k]);
+        for (int t = 0; t < K; ++t) {
+            double w = 0.0;
+            for (int k = 0; k < K; ++k) w = std::max(w, v_ring[(size_t)t * K + k]);
+            c += w;
+        }
+        return a + b + c;
+    };
+    auto fits = [&](int d) { return !(cl.m_static[d] + mem_act(mo, T, d, group_of[d]) > cl.m[d]); };
+    double C = total(na, a2a, ring);
     bool improved = true;
     for (int it = 0; improved && it < i_max; ++it) {
         improved = false;
-        for (int a = 0; a < cl.n && !improved; ++a)
-            for (int b = 0; b < cl.n && !improved; ++b) {
+        for (int a = 0; a < n && !improved; ++a)
+            for (int b = 0; b < n && !improved; ++b) {
                 if (a == b) continue;
                 const int ka = group_of[a], kb = group_of[b];
                 if (!(ka == kb || ((kb - ka) % K + K) % K == 1 || ((ka - kb) % K + K) % K == 1)) continue;
                 if (T.s_pre[a] >= move_tokens && (ka == kb || T.l_group[ka] > move_tokens)) {
-                    Sched m = T;
-                    m.s_pre[a] -= move_tokens; m.s_pre[b] += move_tokens;
-                    if (ka != kb) { m.l_group[ka] -= move_tokens; m.l_group[kb] += move_tokens; }
-                    if (feasible(cl, mo, m)) {
-                        const double c2 = t_blk(cl, mo, m);
-                        if (c2 < C) { T = m; C = c2; improved = true; break; }
+                    T.s_pre[a] -= move_tokens; T.s_pre[b] += move_tokens;
+                    if (ka != kb) { T.l_group[ka] -= move_tokens; T.l_group[kb] += move_tokens; }
+                    bool ok = fits(a) && fits(b);
+                    if (ok && ka != kb) {
+                        for (int d : T.groups[ka]) ok = ok && fits(d);
+                        for (int d : T.groups[kb]) ok = ok && fits(d);
                     }
+                    if (ok) {
+                        na2 = na; a2a2 = a2a; ring2 = ring;
+                        na2[a] = t_nonattn(cl, mo, T, a); na2[b] = t_nonattn(cl, mo, T, b);
+                        a2a2[ka] = t_a2a(cl, mo, T, ka);
+                        if (kb != ka) {
+                            a2a2[kb] = t_a2a(cl, mo, T, kb);
+                            for (int t = 0; t < K; ++t) {
+                                ring2[(size_t)t * K + ka] = group_step(cl, mo, T, t, ka);
+                                ring2[(size_t)t * K + kb] = group_step(cl, mo, T, t, kb);
+                            }
+                            for (int k = 0; k < K; ++k) {     // groups that receive one of the two blocks at some step
+                                const int ta = ((k - ka) % K + K) % K, tb = ((k - kb) % K + K) % K;
+                                ring2[(size_t)ta * K + k] = group_step(cl, mo, T, ta, k);
+                                ring2[(size_t)tb * K + k] = group_step(cl, mo, T, tb, k);
+                            }
+                        }
+                        const double c2 = total(na2, a2a2, ring2);
+                        if (c2 < C) { na.swap(na2); a2a.swap(a2a2); ring.swap(ring2); C = c2; improved = true; break; }
+                    }
+                    T.s_pre[a] += move_tokens; T.s_pre[b] -= move_tokens;
+                    if (ka != kb) { T.l_group[ka] += move_tokens; T.l_group[kb] -= move_tokens; }
                 }
                 if (ka == kb && T.n_heads[a] >= 1) {
-                    Sched m = T;
-                    m.n_heads[a] -= 1; m.n_heads[b] += 1;
-                    if (feasible(cl, mo, m)) {
-                        const double c2 = t_blk(cl, mo, m);
-                        if (c2 < C) { T = m; C = c2; improved = true; break; }
+                    T.n_heads[a] -= 1; T.n_heads[b] += 1;
+                    if (fits(a) && fits(b)) {
+                        a2a2 = a2a; ring2 = ring;
+                        a2a2[ka] = t_a2a(cl, mo, T, ka);
+                        const int succ = (ka + 1) % K;
+                        for (int t = 0; t < K; ++t) {
+                            ring2[(size_t)t * K + ka] = group_step(cl, mo, T, t, ka);
+                            ring2[(size_t)t * K + succ] = group_step(cl, mo, T, t, succ);
+                        }
+                        const double c2 = total(na, a2a2, ring2);
+                        if (c2 < C) { a2a.swap(a2a2); ring.swap(ring2); C = c2; improved = true; break; }
                     }
+                    T.n_heads[a] += 1; T.n_heads[b] -= 1;
                 }
             }
     }
