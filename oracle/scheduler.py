@@ -13,7 +13,7 @@ sequence length L_k, pre-A2A shard s_d and head count n_d:
     T_blk        = max_d T_nonattn + max_k T_A2A + sum_t T_step(t)                             (Sec. 4.2)
     Mem_act(d)   = B P (gamma s_d H + 2 L_G(d) n_d d_h) <= m_d - M_static_d                    (App. A.2)
 
-Readings where the paper is silent or at odds with itself (each is also listed in the design notes):
+Readings where the paper is silent or at odds with itself:
  r1  Every A2A group holds all heads: sum_{d in G_k} n_d = N_heads for every k (the text's "globally"
      cannot hold once there is more than one group, since each group attends with all heads over its block).
  r2  Groups form a ring in the order of their smallest device index; at step t group k receives the KV
