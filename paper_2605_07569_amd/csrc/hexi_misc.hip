@@ -21,18 +21,21 @@ __global__ void __launch_bounds__(256) merge_kernel(long long n_vec, int nq, int
     const long long li = (long long)h * n_rows + row;
     const float a = lse_acc[li], b = lse_part[li];
     const float m = fmaxf(a, b);
-    float4 oa = reinterpret_cast<const float4*>(o_acc)[idx];
+    typedef float nt_f32x4 __attribute__((ext_vector_type(4)));
+    const nt_f32x4 oa_v = __builtin_nontemporal_load(reinterpret_cast<const nt_f32x4*>(o_acc) + idx);
+    float4 oa = make_float4(oa_v[0], oa_v[1], oa_v[2], oa_v[3]);
     float4 r;
     if (m == -INFINITY) {
         r = make_float4(0.f, 0.f, 0.f, 0.f);
     } else {
-        const float4 ob = reinterpret_cast<const float4*>(o_part)[idx];
+        const nt_f32x4 ob_v = __builtin_nontemporal_load(reinterpret_cast<const nt_f32x4*>(o_part) + idx);
+        const float4 ob = make_float4(ob_v[0], ob_v[1], ob_v[2], ob_v[3]);
         const float ea = expf(a - m), eb = expf(b - m);
         const float inv = 1.0f / (ea + eb);
         const float wa = ea * inv, wb = eb * inv;
         r = make_float4(wa * oa.x + wb * ob.x, wa * oa.y + wb * ob.y, wa * oa.z + wb * ob.z, wa * oa.w + wb * ob.w);
     }
-    reinterpret_cast<float4*>(o_acc)[idx] = r;
+    { const nt_f32x4 r_v = {r.x, r.y, r.z, r.w}; __builtin_nontemporal_store(r_v, reinterpret_cast<nt_f32x4*>(o_acc) + idx); }
     if (OUT_MODE == 1) reinterpret_cast<float4*>(o_final)[idx] = r;
     if (OUT_MODE == 2) {
         __hip_bfloat16 t[4] = {__float2bfloat16(r.x), __float2bfloat16(r.y), __float2bfloat16(r.z), __float2bfloat16(r.w)};
@@ -83,7 +86,9 @@ __global__ void __launch_bounds__(256) delta_kernel(long long lq, int nq, const 
     long long row = 0; int h = 0;
     if (valid) {
         row = rh / nq; h = (int)(rh - row * nq);
-        const float4 ov = reinterpret_cast<const float4*>(o + rh * D)[c4];
+        typedef float nt_f32x4 __attribute__((ext_vector_type(4)));
+        const nt_f32x4 ov_v = __builtin_nontemporal_load(reinterpret_cast<const nt_f32x4*>(o + rh * D) + c4);
+        const float4 ov = make_float4(ov_v[0], ov_v[1], ov_v[2], ov_v[3]);
         const T* p = d_o + row * stride_tok + h * stride_head + c4 * 4;
         float g0, g1, g2, g3;
         if constexpr (sizeof(T) == 4) {
