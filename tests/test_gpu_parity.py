@@ -127,12 +127,12 @@ def test_dkdv_head_runs(run_len, monkeypatch):
     _run_and_compare(w, seed=22, fused=False)
 
 
-def _random_case(rng, i):
+def _random_case(rng, i, l_range=(200, 1400), max_heads=8):
     """A seeded random shard: the sequence [0, L) cut into pieces, each piece dealt to one of 1-4 chunks, the q
     shard takes 1-3 pieces; random head counts and kv map."""
     dtype = "bf16" if i % 3 else "f32"
     d = 128 if dtype == "bf16" else int(rng.choice([64, 128]))
-    L = int(rng.integers(200, 1400))
+    L = int(rng.integers(*l_range))
     n_pieces = int(rng.integers(2, 9))
     cuts = sorted(set(int(c) for c in rng.integers(1, L, size=n_pieces - 1)))
     edges = [0] + cuts + [L]
@@ -147,7 +147,7 @@ def _random_case(rng, i):
     own = sorted(rng.choice(len(pieces), size=min(len(pieces), int(rng.integers(1, 4))), replace=False).tolist())
     q_segs = [pieces[k] for k in own]
     nkv = int(rng.integers(1, 4))
-    nq = int(rng.integers(nkv, 9))
+    nq = int(rng.integers(nkv, max(nkv, max_heads) + 1))
     kv_of_q = sorted(int(x) for x in rng.integers(0, nkv, size=nq)) if rng.random() < 0.5 else [int(x) for x in rng.integers(0, nkv, size=nq)]
     return _custom(f"rand{i}_{dtype}", dtype, nq, nkv, d, L, q_segs, chunks, kv_of_q=kv_of_q)
 
@@ -157,6 +157,14 @@ def test_randomized_small_shards():
     for i in range(16):
         w = _random_case(rng, i)
         _run_and_compare(w, seed=100 + i, fused=bool(i % 2))
+
+
+def test_randomized_longer_shards():
+    # the same generator at lengths that span many q tiles (256 rows) and key tiles (64 / 128 keys) per workgroup
+    rng = np.random.default_rng(7569)
+    for i in range(8):
+        w = _random_case(rng, 3 * i + 1, l_range=(2500, 6000), max_heads=4)     # bf16 cases
+        _run_and_compare(w, seed=200 + i, fused=bool(i % 2))
 
 
 def test_strided_inputs_and_accumulate_flags():
