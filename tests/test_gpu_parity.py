@@ -167,7 +167,12 @@ def test_randomized_longer_shards():
         _run_and_compare(w, seed=200 + i, fused=bool(i % 2))
 
 
-def test_strided_inputs_and_accumulate_flags():
+@pytest.mark.parametrize("run_len", [0, 1, 2])
+def test_strided_inputs_and_accumulate_flags(run_len, monkeypatch):
+    # (also with forced dK/dV head runs: whole groups in one workgroup add to the running dk/dv without
+    # atomics, split groups with them)
+    if run_len:
+        monkeypatch.setenv("HEXI_DKDV_RUN_LEN", str(run_len))
     # q/dO and k/v are slices of wider buffers (token and head strides larger than dense)
     w = _custom("strided", "bf16", 4, 2, 128, 512, [(128, 384)], [[(0, 256)], [(256, 256)]])
     inputs = wl.make_inputs(w, 5)
