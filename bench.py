@@ -28,6 +28,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", type=int, default=2, help="shard configuration 1..5 (default 2: the 3B-like zigzag shard)")
+    ap.add_argument("--head-dim", type=int, default=0,
+                    help="variant run: the same shard with this head_dim (64 or 128) instead of the configuration's own")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a kernel of known HBM traffic) before the timed "
@@ -49,6 +51,10 @@ def main():
     hexi.load()   # raises if the HIP library is not built: no fallback path exists
     torch.cuda.set_device(0)
     w = wl.config(args.workload)
+    if args.head_dim and args.head_dim != w.head_dim:
+        import dataclasses
+        w = dataclasses.replace(w, head_dim=args.head_dim, name=f"{w.name}_d{args.head_dim}",
+                                note=w.note + f" (variant: head_dim {args.head_dim})")
     inputs = wl.make_inputs(w)
     run = replay.ShardRun(w, inputs, "cuda:0", fused_merge=True)
     n_pairs_chunk = [hexi.hexi_shard_mask(w.q_segs, ch, want_pos=False)["n_pairs"] for ch in w.chunks]

@@ -69,7 +69,7 @@ typedef struct { int32_t n_segs; const hexi_seg* segs; } hexi_range;
 
 typedef struct {
     int32_t dtype;              /* HEXI_BF16 | HEXI_F32: element type of q, k, v, d_o */
-    int32_t head_dim;           /* 128 (bf16); 64 or 128 (f32) */
+    int32_t head_dim;           /* 64 or 128 */
     int32_t n_q_heads;          /* local (assigned) q heads, packed */
     int32_t n_kv_heads;         /* local kv heads, packed */
     const int32_t* kv_of_q;     /* HOST [n_q_heads]: local kv head read by each local q head;

@@ -109,8 +109,7 @@ static int build_geom(const hexi_attn_desc* d, const hexi_range* q_range, const 
 {
     if (!d) return fail(HEXI_EINVAL, "null descriptor");
     if (d->dtype != HEXI_BF16 && d->dtype != HEXI_F32) return fail(HEXI_EUNSUPPORTED, "dtype %d not supported", d->dtype);
-    const bool ok_dim = d->dtype == HEXI_BF16 ? (d->head_dim == 128) : (d->head_dim == 64 || d->head_dim == 128);
-    if (!ok_dim) return fail(HEXI_EUNSUPPORTED, "head_dim %d not supported for dtype %d", d->head_dim, d->dtype);
+    if (d->head_dim != 64 && d->head_dim != 128) return fail(HEXI_EUNSUPPORTED, "head_dim %d not supported (64 or 128)", d->head_dim);
     if (d->n_q_heads < 1 || d->n_kv_heads < 1 || d->n_q_heads > HEXI_MAX_HEADS || d->n_kv_heads > d->n_q_heads)
         return fail(HEXI_EINVAL, "head counts nq=%d nkv=%d invalid (1 <= nkv <= nq <= %d)", d->n_q_heads, d->n_kv_heads, HEXI_MAX_HEADS);
     if (!(d->softmax_scale > 0.f) || !std::isfinite(d->softmax_scale)) return fail(HEXI_EINVAL, "softmax_scale must be positive and finite");

@@ -1,5 +1,5 @@
-// bf16 backward ring step, dK / dV part, for gfx950: one workgroup of 8 wavefronts per (128-key tile, q head),
-// one workgroup per CU.
+// bf16 backward ring step, dK / dV part, for gfx950 (head_dim D = 128 or 64): one workgroup of 8 wavefronts per
+// (128-key tile, run of q heads), one workgroup per CU.
 //
 // The workgroup keeps its K and V rows in registers as MFMA operands and its dK / dV tiles in accumulators
 // while it sweeps the 64-row q tiles that can see the key tile.  Per q tile: S = Q K^T and dP = dO V^T (keys
@@ -12,12 +12,12 @@
 // SIMD, alternate between a matrix phase and a vector phase with one workgroup barrier per phase, group 1 one
 // phase behind group 0, so that every SIMD always has one wavefront issuing only MFMAs (and their LDS reads)
 // and one issuing only VALU work.  Two wavefronts per SIMD leave 256 registers per wavefront, too few for
-// 32 keys x 128 columns of dK and dV (128 registers) next to the K / V fragments (64): the wavefronts of a
+// 32 keys x 128 columns of dK and dV (128 registers at D = 128) next to the K / V fragments (64): the wavefronts of a
 // group therefore work in pairs on 32 keys.  Each of the two computes S, dP, P, dS for one 32-row half of
 // the q tile; then one of them accumulates dV and the other dK over all 64 rows, each taking its partner's
 // half of the operand it needs (P^T for dV, dS^T for dK; bf16 fragments, 2 KB per wavefront) from LDS.  No
 // product is computed twice, and the accumulators shrink to 64 registers.
-//   M(i): dV += P^T dO or dK += dS^T Q of tile i-1 (16 MFMAs), then S and dP of tile i (16 MFMAs);
+//   M(i): dV += P^T dO or dK += dS^T Q of tile i-1 (D / 8 MFMAs), then S and dP of tile i (D / 8 MFMAs);
 //   V(i): P and dS of tile i, rounded to bf16 operand slots; the partner's fragments go to the exchange area.
 // Q / dO tiles are triple-buffered in LDS (padded, row-permuted layout: conflict-free row and transposed reads
 // from single base registers) and fetched two tiles ahead with direct global->LDS loads: Q by group 1 at the
@@ -35,25 +35,26 @@
 
 namespace {
 
-constexpr int D = 128;
 constexpr int WG_KEYS = 128;     // keys per workgroup: 2 groups x 2 pairs x 32
 constexpr int TM = 64;           // q rows per tile
 constexpr int NB = 3;            // LDS buffers per tensor
-constexpr int DMA_PER_WAVE = 5;  // most tile transfers a wavefront issues per tile (17 per tile over 4 wavefronts)
 constexpr float LOG2E = 1.4426950408889634f;
 
-struct BwdSmem {
-    unsigned char q[NB][P16_TILE_BYTES];   // 3 x 17 KB
-    unsigned char g[NB][P16_TILE_BYTES];   // dO, 3 x 17 KB
+template <int D> struct BwdSmem {
+    unsigned char q[NB][p16_tile_bytes(D)];   // 3 x 17 KB (D = 128) or 3 x 9 KB
+    unsigned char g[NB][p16_tile_bytes(D)];   // dO, the same
     unsigned char xch[8][2048];            // per wavefront: the two fragments its partner needs (64 lanes x 16 B each)
     float lse[NB][TM];
     float delta[NB][TM];
     int qpos[8][TM];                       // row positions of the tiles that need a mask, written two tiles ahead
 };
 
-// LDS reads of matrix-phase step st: two transposed reads below 16 (+ a fragment of the partner's at steps 8
-// and 12), one row read from 16 on
-__host__ __device__ constexpr int reads_of(int st) { return st < 16 ? 2 + ((st == 8 || st == 12) ? 1 : 0) : 1; }
+// LDS reads of matrix-phase step st (ndb = D / 32 column blocks): two transposed reads below 4 ndb (+ a fragment
+// of the partner's at steps 2 ndb and 3 ndb), one row read from there on
+__host__ __device__ constexpr int reads_of(int st, int ndb)
+{
+    return st < 4 * ndb ? 2 + ((st == 2 * ndb || st == 3 * ndb) ? 1 : 0) : 1;
+}
 
 // Runs of q heads: run r covers len[r] heads starting at first[r], linked through next[] (all read kv head
 // kv_of_q[first[r]]).
@@ -62,11 +63,17 @@ struct HeadRuns {
     signed char first[HEXI_MAX_HEADS], len[HEXI_MAX_HEADS], next[HEXI_MAX_HEADS];
 };
 
-template <bool ATOMIC_DKV>
+template <int D, bool ATOMIC_DKV>
 __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, const HeadRuns runs, const int n_kv_tiles)
 {
+    static_assert(D == 64 || D == 128, "head_dim 64 or 128");
+    constexpr int NKS = D / 16;     // 16-wide contraction steps across the head dimension
+    constexpr int NDB = D / 32;     // 32-column blocks of dK / dV
+    constexpr int P16_ROW_BYTES = p16_row_bytes(D), P16_TILE_BYTES = p16_tile_bytes(D);
+    constexpr int N_XFER = P16_TILE_BYTES / 1024;          // wave-wide transfers per tile: 17 or 9
+    constexpr int DMA_PER_WAVE = (N_XFER + 3) / 4;         // most transfers a wavefront issues per tile: 5 or 3
     const AttnGeom& g = a.g;
-    __shared__ __attribute__((aligned(1024))) BwdSmem sm;
+    __shared__ __attribute__((aligned(1024))) BwdSmem<D> sm;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -106,21 +113,21 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
 
     // K^T and V^T operand fragments of S = Q K^T and dP = dO V^T: lane (key l32, half hh) holds
     // d = 16*ks + 8*hh .. +7 of its key
-    bf16x8 kf[8], vf[8];
+    bf16x8 kf[NKS], vf[NKS];
     {
         const long long off = (long long)my_col_c * g.kv_stride_tok + 8 * hh;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
+        for (int ks = 0; ks < NKS; ++ks) {
             kf[ks] = *reinterpret_cast<const bf16x8*>(k + off + 16 * ks);
             vf[ks] = *reinterpret_cast<const bf16x8*>(v + off + 16 * ks);
         }
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) { pin(kf[ks]); pin(vf[ks]); }
+        for (int ks = 0; ks < NKS; ++ks) { pin(kf[ks]); pin(vf[ks]); }
     }
-    // dV (role 0) or dK (role 1) of the pair's 32 keys: four 32-column blocks
-    f32x16 acc[4];
+    // dV (role 0) or dK (role 1) of the pair's 32 keys: NDB 32-column blocks
+    f32x16 acc[NDB];
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
     const float scale_log2 = g.scale * LOG2E;
@@ -140,8 +147,7 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
     // A transfer is one wave-wide instruction: lane L writes the 16 bytes at (transfer * 1024 + 16 * L) of the
     // tile's LDS image and reads the 16-byte piece of the q row that belongs there (the pad piece re-reads
     // piece 0).  Wavefront wg4 issues the transfers wg4, wg4 + 4, ... below the tile's
-    // transfer count (5 or 4 of them).
-    constexpr int N_XFER = P16_TILE_BYTES / 1024;
+    // transfer count (DMA_PER_WAVE of them, or one fewer).
     uint32_t fetch_off[DMA_PER_WAVE];   // byte offsets from the tile's first row
     int fetch_row[DMA_PER_WAVE];
 #pragma unroll
@@ -150,7 +156,7 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
         int r = pos / P16_ROW_BYTES, c = (pos - r * P16_ROW_BYTES) >> 4;
         r = p16_row(r);     // the permutation is its own inverse: LDS row -> q row
         if (wg4 + 4 * i >= N_XFER) r = 0;
-        if (c >= 16) c = 0;
+        if (c >= D / 8) c = 0;
         fetch_row[i] = r;
         fetch_off[i] = 2u * (uint32_t)(r * (int)g.q_stride_tok + c * 8);
     }
@@ -217,11 +223,13 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
     f32x16 s, dp;
     bf16x8 own[2];     // own operand fragments (P^T for the dV wavefront, dS^T for the dK wavefront)
 
-    // Matrix phase on buffers (B + NB - 1) % NB (previous tile) and B (this tile).  Steps 0..15: this
-    // wavefront's product (dV += P^T dO or dK += dS^T Q) of the previous tile: steps 0..7 contract over its own
-    // 32 rows (fragments in registers), steps 8..15 over its partner's (fragments from LDS); 16-row step
-    // (st / 4) % 2, column block st % 4.  Steps 16..31: S and dP of this tile's 32-row half, alternating,
-    // ks = (st - 16) / 2.  [FIRST, LAST) selects the steps; operand fragments are requested PF steps ahead.
+    // Matrix phase on buffers (B + NB - 1) % NB (previous tile) and B (this tile).  Steps 0..NACC-1: this
+    // wavefront's product (dV += P^T dO or dK += dS^T Q) of the previous tile: the first half of them contract
+    // over its own 32 rows (fragments in registers), the second half over its partner's (fragments from LDS);
+    // 16-row step (st / NDB) % 2, column block st % NDB.  Steps NACC..NST-1: S and dP of this tile's 32-row half,
+    // alternating, ks = (st - NACC) / 2.  [FIRST, LAST) selects the steps; operand fragments are requested PF
+    // steps ahead.
+    constexpr int NACC = 4 * NDB, NST = NACC + 2 * NKS;
     auto m_phase = [&](auto bc, auto first_c, auto last_c) __attribute__((always_inline)) {
         constexpr int B = decltype(bc)::value, FIRST = decltype(first_c)::value, LAST = decltype(last_c)::value;
         constexpr int PF = 3, NS = PF + 1;   // a fragment's registers are busy from its request until its MFMA
@@ -231,14 +239,14 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
         bf16x8 pfr[2];                       // the partner's two fragments
         auto issue = [&](auto stc) __attribute__((always_inline)) {
             constexpr int st = decltype(stc)::value, slot = (st - FIRST) % NS;
-            if constexpr (st < 16) {
-                constexpr int half = st >> 3, kq = (st >> 2) & 1, db = st & 3;
-                if constexpr (st == 8 || st == 12) lds_issue_b128<kq * 1024>(pfr[kq], xch_partner);
+            if constexpr (st < NACC) {
+                constexpr int half = st / (2 * NDB), kq = (st / NDB) & 1, db = st % NDB;
+                if constexpr (st == 2 * NDB || st == 3 * NDB) lds_issue_b128<kq * 1024>(pfr[kq], xch_partner);
                 constexpr int off = BP * P16_TILE_BYTES + 16 * kq * P16_ROW_BYTES + 64 * db;
                 lds_issue_tr16<off>(ta[slot], tr_addr[half]);
                 lds_issue_tr16<off + 2 * P16_ROW_BYTES>(tb[slot], tr_addr[half]);
             } else {
-                constexpr int which = (st - 16) & 1, ks = (st - 16) >> 1;
+                constexpr int which = (st - NACC) & 1, ks = (st - NACC) >> 1;
                 lds_issue_b128<B * P16_TILE_BYTES + 32 * ks>(nb[slot], nat_addr[which]);
             }
         };
@@ -246,12 +254,12 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
             constexpr int st = decltype(stc)::value, slot = (st - FIRST) % NS;
             if constexpr (st + PF < LAST) issue(IC<st + PF>{});
             constexpr int hi = st + PF < LAST ? st + PF : LAST - 1;
-            constexpr int younger = (hi >= st + 1 ? reads_of(st + 1) : 0) + (hi >= st + 2 ? reads_of(st + 2) : 0) +
-                                    (hi >= st + 3 ? reads_of(st + 3) : 0);
+            constexpr int younger = (hi >= st + 1 ? reads_of(st + 1, NDB) : 0) + (hi >= st + 2 ? reads_of(st + 2, NDB) : 0) +
+                                    (hi >= st + 3 ? reads_of(st + 3, NDB) : 0);
             static_assert(PF == 3, "the sum above covers three steps");
             const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            if constexpr (st < 16) {
-                constexpr int half = st >> 3, kq = (st >> 2) & 1, db = st & 3;
+            if constexpr (st < NACC) {
+                constexpr int half = st / (2 * NDB), kq = (st / NDB) & 1, db = st % NDB;
                 if constexpr (half == 0) {
                     lds_wait<younger>(ta[slot], tb[slot]);
                     acc[db] = mfma32(own[kq], join_halves(ta[slot], tb[slot]), acc[db]);
@@ -261,7 +269,7 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
                     acc[db] = mfma32(pfr[kq], join_halves(ta[slot], tb[slot]), acc[db]);
                 }
             } else {
-                constexpr int which = (st - 16) & 1, ks = (st - 16) >> 1;
+                constexpr int which = (st - NACC) & 1, ks = (st - NACC) >> 1;
                 lds_wait<younger>(nb[slot]);
                 if constexpr (which == 0) s = mfma32(nb[slot], kf[ks], ks == 0 ? zero : s);
                 else dp = mfma32(nb[slot], vf[ks], ks == 0 ? zero : dp);
@@ -329,29 +337,29 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
             else v_phase(i % NB, i & 7, std::false_type{});
             if (++proc_t == n_all) proc_t = 0;
         };
-        enter_m(0); m_phase(IC<0>{}, IC<16>{}, IC<32>{}); vector_part(0);
+        enter_m(0); m_phase(IC<0>{}, IC<NACC>{}, IC<NST>{}); vector_part(0);
         // tiles 1 .. n_seq-1: three at a time in a straight line (buffer = i % 3 is then a compile-time constant
         // and no accumulator passes through a control-flow merge), then the remaining ones through a switch
         int i = 1;
         for (; i + 2 < n_seq; i += 3) {
-            enter_m(i);     m_phase(IC<1>{}, IC<0>{}, IC<32>{}); vector_part(i);
-            enter_m(i + 1); m_phase(IC<2>{}, IC<0>{}, IC<32>{}); vector_part(i + 1);
-            enter_m(i + 2); m_phase(IC<0>{}, IC<0>{}, IC<32>{}); vector_part(i + 2);
+            enter_m(i);     m_phase(IC<1>{}, IC<0>{}, IC<NST>{}); vector_part(i);
+            enter_m(i + 1); m_phase(IC<2>{}, IC<0>{}, IC<NST>{}); vector_part(i + 1);
+            enter_m(i + 2); m_phase(IC<0>{}, IC<0>{}, IC<NST>{}); vector_part(i + 2);
         }
         for (; i < n_seq; ++i) {
             enter_m(i);
             switch (i % NB) {
-                case 0: m_phase(IC<0>{}, IC<0>{}, IC<32>{}); break;
-                case 1: m_phase(IC<1>{}, IC<0>{}, IC<32>{}); break;
-                default: m_phase(IC<2>{}, IC<0>{}, IC<32>{}); break;
+                case 0: m_phase(IC<0>{}, IC<0>{}, IC<NST>{}); break;
+                case 1: m_phase(IC<1>{}, IC<0>{}, IC<NST>{}); break;
+                default: m_phase(IC<2>{}, IC<0>{}, IC<NST>{}); break;
             }
             vector_part(i);
         }
         enter_m(n_seq);
         switch (n_seq % NB) {
-            case 0: m_phase(IC<0>{}, IC<0>{}, IC<16>{}); break;
-            case 1: m_phase(IC<1>{}, IC<0>{}, IC<16>{}); break;
-            default: m_phase(IC<2>{}, IC<0>{}, IC<16>{}); break;
+            case 0: m_phase(IC<0>{}, IC<0>{}, IC<NACC>{}); break;
+            case 1: m_phase(IC<1>{}, IC<0>{}, IC<NACC>{}); break;
+            default: m_phase(IC<2>{}, IC<0>{}, IC<NACC>{}); break;
         }
         if (grp == 0) wg_barrier();
     }
@@ -360,7 +368,7 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
     float* out = role ? a.dk : a.dv;
     const float out_scale = role ? g.scale : 1.0f;
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int col = wcol0 + 8 * (r >> 2) + 4 * hh + (r & 3);
@@ -432,14 +440,20 @@ hipError_t hexi_launch_bwd_bf16(const BwdArgs& a, hipStream_t s)
         }
         const unsigned grid = (unsigned)(runs.n * n_kv_tiles);
         if ((shared || unused) && !a.accumulate) {
-            const long long n = (long long)a.g.lc * a.g.nkv * D;
+            const long long n = (long long)a.g.lc * a.g.nkv * a.g.d;
             hipError_t e = hexi_launch_fill_f32(a.dk, n, 0.f, s);
             if (e == hipSuccess) e = hexi_launch_fill_f32(a.dv, n, 0.f, s);
             if (e != hipSuccess) return e;
         }
+        if (a.g.d != 128 && a.g.d != 64) return hipErrorInvalidValue;
         if (grid > 0) {
-            if (shared) bwd_dkdv_bf16_kernel<true><<<grid, 512, 0, s>>>(a, runs, n_kv_tiles);
-            else bwd_dkdv_bf16_kernel<false><<<grid, 512, 0, s>>>(a, runs, n_kv_tiles);
+            if (a.g.d == 128) {
+                if (shared) bwd_dkdv_bf16_kernel<128, true><<<grid, 512, 0, s>>>(a, runs, n_kv_tiles);
+                else bwd_dkdv_bf16_kernel<128, false><<<grid, 512, 0, s>>>(a, runs, n_kv_tiles);
+            } else {
+                if (shared) bwd_dkdv_bf16_kernel<64, true><<<grid, 512, 0, s>>>(a, runs, n_kv_tiles);
+                else bwd_dkdv_bf16_kernel<64, false><<<grid, 512, 0, s>>>(a, runs, n_kv_tiles);
+            }
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;

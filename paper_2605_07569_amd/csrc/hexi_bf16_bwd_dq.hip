@@ -1,5 +1,5 @@
-// bf16 backward ring step, dQ part, for gfx950: one workgroup of 8 wavefronts per (256-row q tile, q head),
-// one workgroup per CU; the q tile's dQ stays in accumulators while the chunk's keys stream past, so dQ needs
+// bf16 backward ring step, dQ part, for gfx950 (head_dim D = 128 or 64): one workgroup of 8 wavefronts per
+// (256-row q tile, q head), one workgroup per CU; the q tile's dQ stays in accumulators while the chunk's keys stream past, so dQ needs
 // no atomics and its summation order is fixed.
 //
 // Everything is computed transposed, as in the forward kernel, so that every lane owns one query row and the
@@ -13,7 +13,7 @@
 // phase behind group 0, so that every SIMD always has one wavefront issuing only MFMAs (and their LDS reads)
 // and one issuing only VALU work.  A phase covers a 32-key block (half a 64-key LDS tile), which keeps the
 // scores and dP of one block only in registers:
-//   M(b): dQ^T += K^T dS^T of block b-1 (8 MFMAs), then S^T and dP^T of block b (16 MFMAs);
+//   M(b): dQ^T += K^T dS^T of block b-1 (D / 16 MFMAs), then S^T and dP^T of block b (D / 8 MFMAs);
 //   V(b): P^T and dS^T of block b, dS^T rounded to bf16 operand slots.
 // The vector-phase group also issues the direct global->LDS loads: during the first block of tile j, group 1
 // requests K of tile j + 3 and group 0 requests V of tile j + 3 (four LDS buffers per tensor).
@@ -22,28 +22,33 @@
 
 namespace {
 
-constexpr int D = 128;
 constexpr int TN = 64;             // keys per LDS tile (two 32-key blocks)
 constexpr int NB = 4;              // LDS buffers per tensor
 constexpr int GROUP_ROWS = 128;    // q rows per wavefront group (32 per wavefront)
 constexpr int WG_ROWS = 256;       // q rows per workgroup
 constexpr int AHEAD = 3;           // tile j + 3 is requested during tile j
-constexpr int DMA_PER_WAVE = 5;    // most transfers a wavefront issues per tile (17 per tile over 4 wavefronts)
-constexpr int STAGE_STRIDE = D + 4;   // floats per staged output row (epilogue)
 constexpr float LOG2E = 1.4426950408889634f;
 
-struct DqSmem {
-    unsigned char k[NB][P16_TILE_BYTES];   // 4 x 17 KB
-    unsigned char v[NB][P16_TILE_BYTES];   // 4 x 17 KB
+template <int D> struct DqSmem {
+    unsigned char k[NB][p16_tile_bytes(D)];   // 4 x 17 KB (D = 128) or 4 x 9 KB
+    unsigned char v[NB][p16_tile_bytes(D)];
     int kpos[2 * NB][TN];     // key positions of the tiles that need a mask, written AHEAD tiles ahead
-    // the epilogue stages 8 x (32 x 132) floats over the start of this struct
+    // the epilogue stages 8 x (32 x (D + 4)) floats over the start of this struct
 };
-static_assert(sizeof(DqSmem) >= 8 * 32 * STAGE_STRIDE * 4, "epilogue staging does not fit");
 
+template <int D>
 __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const int n_q_tiles)
 {
+    static_assert(D == 64 || D == 128, "head_dim 64 or 128");
+    constexpr int NKS = D / 16;     // 16-wide contraction steps across the head dimension
+    constexpr int NDB = D / 32;     // 32-column blocks of dQ
+    constexpr int P16_ROW_BYTES = p16_row_bytes(D), P16_TILE_BYTES = p16_tile_bytes(D);
+    constexpr int N_XFER = P16_TILE_BYTES / 1024;          // wave-wide transfers per tile: 17 or 9
+    constexpr int DMA_PER_WAVE = (N_XFER + 3) / 4;         // most transfers a wavefront issues per tile: 5 or 3
+    constexpr int STAGE_STRIDE = D + 4;                    // floats per staged output row (epilogue)
+    static_assert(sizeof(DqSmem<D>) >= 8 * 32 * STAGE_STRIDE * 4, "epilogue staging does not fit");
     const AttnGeom& g = a.g;
-    __shared__ __attribute__((aligned(1024))) DqSmem sm;
+    __shared__ __attribute__((aligned(1024))) DqSmem<D> sm;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -81,14 +86,14 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
     if (NT == 0) return;     // this q tile sees nothing of the chunk: dq_acc unchanged
 
     // Q^T and dO^T operand fragments: lane (row l32, half hh) holds d = 16*ks + 8*hh .. +7
-    bf16x8 qf[8], gf[8];
+    bf16x8 qf[NKS], gf[NKS];
     float neg_lse2, delta;
     {
         const long long off = (long long)my_row_c * g.q_stride_tok + (long long)h * g.q_stride_head + 8 * hh;
         const uint16_t* qp = static_cast<const uint16_t*>(a.q) + off;
         const uint16_t* gp = static_cast<const uint16_t*>(a.d_o) + off;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
+        for (int ks = 0; ks < NKS; ++ks) {
             qf[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
             gf[ks] = *reinterpret_cast<const bf16x8*>(gp + 16 * ks);
         }
@@ -97,17 +102,16 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
         neg_lse2 = (my_row < g.lq && l != -INFINITY) ? -l * LOG2E : -INFINITY;
         delta = a.delta[(long long)h * g.lq + my_row_c];
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) { pin(qf[ks]); pin(gf[ks]); }
+        for (int ks = 0; ks < NKS; ++ks) { pin(qf[ks]); pin(gf[ks]); }
         asm volatile("" ::"v"(neg_lse2), "v"(delta));
     }
 
     // Direct global->LDS fetch of one tile by the four wavefronts of a group (group 1: K, group 0: V).  A
     // transfer is one wave-wide instruction: lane L writes the 16 bytes at (transfer * 1024 + 16 * L) of the
     // tile's LDS image and reads the 16-byte piece of the key row that belongs there (the pad piece re-reads
-    // piece 0).  Wavefront wg issues the transfers wg, wg + 4, ... below the tile's transfer count (5 or 4
-    // of them).
-    constexpr int N_XFER = P16_TILE_BYTES / 1024;
-    const int my_xfers = (N_XFER - wg + 3) / 4;     // transfers this wavefront issues per tile: wg, wg + 4, ... (5 or 4)
+    // piece 0).  Wavefront wg issues the transfers wg, wg + 4, ... below the tile's transfer count
+    // (DMA_PER_WAVE of them, or one fewer).
+    const int my_xfers = (N_XFER - wg + 3) / 4;     // transfers this wavefront issues per tile: wg, wg + 4, ...
     uint32_t fetch_off[DMA_PER_WAVE];   // byte offsets from the tile's first key
     int fetch_row[DMA_PER_WAVE];
 #pragma unroll
@@ -116,7 +120,7 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
         int r = pos / P16_ROW_BYTES, c = (pos - r * P16_ROW_BYTES) >> 4;
         r = p16_row(r);     // the permutation is its own inverse: LDS row -> key
         if (wg + 4 * i >= N_XFER) r = 0;
-        if (c >= 16) c = 0;
+        if (c >= D / 8) c = 0;
         fetch_row[i] = r;
         fetch_off[i] = 2u * (uint32_t)(r * (int)g.kv_stride_tok + c * 8);
     }
@@ -160,19 +164,20 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
     ktr_addr[0] = lds_k + (4 * jj + hh) * P16_ROW_BYTES + 2 * (16 * grp2 + 4 * (j16 & 3));
     ktr_addr[1] = ktr_addr[0] + 2 * P16_TILE_BYTES;
 
-    f32x16 dq[4];
+    f32x16 dq[NDB];
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) dq[db][r] = 0.f;
     f32x16 s, dp;
     bf16x8 dsf[2];
     const float c_log2 = g.scale * LOG2E;
 
-    // Matrix phase of block (tile buffer B, half HALF).  Steps 0..7: dQ^T += K^T dS^T of the previous block
-    // (two 16-key steps x four 32-column blocks; the previous block is the other half of the same tile, or
-    // the second half of the tile before).  Steps 8..23: S^T and dP^T of this block, alternating.
+    // Matrix phase of block (tile buffer B, half HALF).  Steps 0..NDQ-1: dQ^T += K^T dS^T of the previous block
+    // (two 16-key steps x NDB 32-column blocks; the previous block is the other half of the same tile, or
+    // the second half of the tile before).  Steps NDQ..NST-1: S^T and dP^T of this block, alternating.
     // [FIRST, LAST) selects the steps; operand fragments are requested PF steps ahead.
+    constexpr int NDQ = 2 * NDB, NST = NDQ + 2 * NKS;
     auto m_phase = [&](auto bc, auto half_c, auto first_c, auto last_c) __attribute__((always_inline)) {
         constexpr int B = decltype(bc)::value, HALF = decltype(half_c)::value;
         constexpr int FIRST = decltype(first_c)::value, LAST = decltype(last_c)::value;
@@ -183,15 +188,15 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
         bf16x8 nb[NS];
         auto issue = [&](auto stc) __attribute__((always_inline)) {
             constexpr int st = decltype(stc)::value, slot = (st - FIRST) % NS;
-            if constexpr (st < 8) {
-                constexpr int u = UP + (st >> 2), db = st & 3;
+            if constexpr (st < NDQ) {
+                constexpr int u = UP + st / NDB, db = st % NDB;
                 constexpr int off = (BP % 2) * P16_TILE_BYTES + 16 * u * P16_ROW_BYTES + 64 * db;
                 lds_issue_tr16<off>(ta[slot], ktr_addr[BP / 2]);
                 lds_issue_tr16<off + 2 * P16_ROW_BYTES>(tb[slot], ktr_addr[BP / 2]);
             } else {
-                constexpr int ks = (st - 8) >> 1;
+                constexpr int ks = (st - NDQ) >> 1;
                 constexpr int off = B * P16_TILE_BYTES + 32 * HALF * P16_ROW_BYTES + 32 * ks;
-                if constexpr (((st - 8) & 1) == 0) lds_issue_b128<off>(nb[slot], knat_addr);
+                if constexpr (((st - NDQ) & 1) == 0) lds_issue_b128<off>(nb[slot], knat_addr);
                 else lds_issue_b128<off>(nb[slot], vnat_addr);
             }
         };
@@ -200,16 +205,16 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
             if constexpr (st + PF < LAST) issue(IC<st + PF>{});
             // LDS reads younger than this step's fragment: those of the next PF steps that exist
             constexpr int hi = st + PF < LAST ? st + PF : LAST - 1;
-            constexpr int n_tr = (hi < 8 ? hi : 7) - (st < 8 ? st : 7);      // steps in (st, hi] below 8
+            constexpr int n_tr = (hi < NDQ ? hi : NDQ - 1) - (st < NDQ ? st : NDQ - 1);      // steps in (st, hi] below NDQ
             constexpr int younger = 2 * n_tr + ((hi - st) - n_tr);
             const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            if constexpr (st < 8) {
+            if constexpr (st < NDQ) {
                 lds_wait<younger>(ta[slot], tb[slot]);
-                dq[st & 3] = mfma32(join_halves(ta[slot], tb[slot]), dsf[st >> 2], dq[st & 3]);
+                dq[st % NDB] = mfma32(join_halves(ta[slot], tb[slot]), dsf[st / NDB], dq[st % NDB]);
             } else {
-                constexpr int ks = (st - 8) >> 1;
+                constexpr int ks = (st - NDQ) >> 1;
                 lds_wait<younger>(nb[slot]);
-                if constexpr (((st - 8) & 1) == 0) s = mfma32(nb[slot], qf[ks], ks == 0 ? zero : s);
+                if constexpr (((st - NDQ) & 1) == 0) s = mfma32(nb[slot], qf[ks], ks == 0 ? zero : s);
                 else dp = mfma32(nb[slot], gf[ks], ks == 0 ? zero : dp);
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -251,7 +256,7 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
     // group 0 enters M of its first block: group 0 (V) waits there, group 1 (K) waits before the vector phase
     // it runs in that same slot, V(2j - 1).  At that point tiles up to min(j + 2, NT - 1) have been requested.
     auto need_tile = [&](int j) __attribute__((always_inline)) {
-        if (j < NT) wait_tiles_in_flight((j + 2 < NT - 1 ? j + 2 : NT - 1) - j, my_xfers);
+        if (j < NT) wait_tiles_in_flight<DMA_PER_WAVE>((j + 2 < NT - 1 ? j + 2 : NT - 1) - j, my_xfers);
     };
     auto enter_m = [&](int blk) __attribute__((always_inline)) {
         if (grp == 0 && (blk & 1) == 0) need_tile(blk >> 1);
@@ -271,13 +276,13 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
         need_tile(0);
         wg_barrier();
     }
-    enter_m(0); m_phase(IC<0>{}, IC<0>{}, IC<8>{}, IC<24>{}); vector_part(0);
-    enter_m(1); m_phase(IC<0>{}, IC<1>{}, IC<0>{}, IC<24>{}); vector_part(1);
+    enter_m(0); m_phase(IC<0>{}, IC<0>{}, IC<NDQ>{}, IC<NST>{}); vector_part(0);
+    enter_m(1); m_phase(IC<0>{}, IC<1>{}, IC<0>{}, IC<NST>{}); vector_part(1);
     // tiles 1 .. NT-1: four at a time in a straight line (buffer = t % 4 is then a compile-time constant and no
     // accumulator passes through a control-flow merge), then the remaining ones through a switch
     auto tile_steps = [&](int t, auto bc) __attribute__((always_inline)) {
-        enter_m(2 * t);     m_phase(bc, IC<0>{}, IC<0>{}, IC<24>{}); vector_part(2 * t);
-        enter_m(2 * t + 1); m_phase(bc, IC<1>{}, IC<0>{}, IC<24>{}); vector_part(2 * t + 1);
+        enter_m(2 * t);     m_phase(bc, IC<0>{}, IC<0>{}, IC<NST>{}); vector_part(2 * t);
+        enter_m(2 * t + 1); m_phase(bc, IC<1>{}, IC<0>{}, IC<NST>{}); vector_part(2 * t + 1);
     };
     int t = 1;
     for (; t + 3 < NT; t += 4) {
@@ -296,20 +301,20 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
     }
     enter_m(2 * NT);
     switch (NT & 3) {
-        case 0: m_phase(IC<0>{}, IC<0>{}, IC<0>{}, IC<8>{}); break;
-        case 1: m_phase(IC<1>{}, IC<0>{}, IC<0>{}, IC<8>{}); break;
-        case 2: m_phase(IC<2>{}, IC<0>{}, IC<0>{}, IC<8>{}); break;
-        default: m_phase(IC<3>{}, IC<0>{}, IC<0>{}, IC<8>{}); break;
+        case 0: m_phase(IC<0>{}, IC<0>{}, IC<0>{}, IC<NDQ>{}); break;
+        case 1: m_phase(IC<1>{}, IC<0>{}, IC<0>{}, IC<NDQ>{}); break;
+        case 2: m_phase(IC<2>{}, IC<0>{}, IC<0>{}, IC<NDQ>{}); break;
+        default: m_phase(IC<3>{}, IC<0>{}, IC<0>{}, IC<NDQ>{}); break;
     }
     if (grp == 0) wg_barrier();
     __syncthreads();   // every wavefront is done with the tiles: LDS is free for the epilogue
 
-    // Epilogue: dq_acc += scale * dQ.  The scaled rows go through LDS (a private 32 x 132-float region per
+    // Epilogue: dq_acc += scale * dQ.  The scaled rows go through LDS (a private 32 x (D + 4)-float region per
     // wavefront, padded against bank conflicts) so that the global read-modify-write is row-contiguous: one
-    // instruction covers two whole 512-byte rows.  Each (row, head) belongs to exactly one workgroup.
+    // instruction covers 1 KB of whole rows (two at D = 128).  Each (row, head) belongs to exactly one workgroup.
     float* stage = reinterpret_cast<float*>(&sm) + wave * (32 * STAGE_STRIDE);
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int b = 0; b < 4; ++b)
             *reinterpret_cast<float4*>(&stage[l32 * STAGE_STRIDE + 32 * db + 8 * b + 4 * hh]) =
@@ -318,19 +323,22 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // lane -> (row within a group of ROWS_PER_INST rows, 16-byte piece of the row)
+    constexpr int LANES_PER_ROW = D / 4, ROWS_PER_INST = 64 / LANES_PER_ROW, N_INST = 32 / ROWS_PER_INST;
+    const int sub_row = lane / LANES_PER_ROW, piece = lane % LANES_PER_ROW;
     const int wrow0 = grow0 + 32 * wg;
-    float* obase = a.dq + ((long long)wrow0 * g.nq + h) * D + 4 * l32;
+    float* obase = a.dq + ((long long)wrow0 * g.nq + h) * D + 4 * piece;
     const long long row_stride = (long long)g.nq * D;
-    float4 old[16];
+    float4 old[N_INST];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int r = 2 * i + hh;
+    for (int i = 0; i < N_INST; ++i) {
+        const int r = ROWS_PER_INST * i + sub_row;
         old[i] = wrow0 + r < g.lq ? *reinterpret_cast<const float4*>(obase + r * row_stride) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int r = 2 * i + hh;
-        const float4 val = *reinterpret_cast<const float4*>(&stage[r * STAGE_STRIDE + 4 * l32]);
+    for (int i = 0; i < N_INST; ++i) {
+        const int r = ROWS_PER_INST * i + sub_row;
+        const float4 val = *reinterpret_cast<const float4*>(&stage[r * STAGE_STRIDE + 4 * piece]);
         float4 o4 = old[i];
         o4.x += val.x; o4.y += val.y; o4.z += val.z; o4.w += val.w;
         if (wrow0 + r < g.lq) *reinterpret_cast<float4*>(obase + r * row_stride) = o4;
@@ -342,6 +350,9 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
 hipError_t hexi_launch_bwd_dq_bf16(const BwdArgs& a, hipStream_t s)
 {
     const int n_q_tiles = (a.g.lq + WG_ROWS - 1) / WG_ROWS;
-    bwd_dq_bf16_kernel<<<(unsigned)(a.g.nq * n_q_tiles), 512, 0, s>>>(a, n_q_tiles);
+    const unsigned grid = (unsigned)(a.g.nq * n_q_tiles);
+    if (a.g.d == 128) bwd_dq_bf16_kernel<128><<<grid, 512, 0, s>>>(a, n_q_tiles);
+    else if (a.g.d == 64) bwd_dq_bf16_kernel<64><<<grid, 512, 0, s>>>(a, n_q_tiles);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }

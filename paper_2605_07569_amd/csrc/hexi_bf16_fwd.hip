@@ -1,12 +1,12 @@
-// bf16 forward ring step for gfx950: one workgroup of 8 wavefronts per (256-row q tile, q head), one
-// workgroup per CU.
+// bf16 forward ring step for gfx950 (head_dim D = 128 or 64): one workgroup of 8 wavefronts per (256-row q
+// tile, q head), one workgroup per CU.
 //
 // Ping-pong schedule.  On this hardware a wavefront that has just issued an MFMA cannot issue its own
 // VALU work for most of the MFMA's duration, but ANOTHER wavefront of the same SIMD can: a wavefront
 // issuing only MFMAs runs the matrix pipe at its full rate while its SIMD partner issues VALU
 // instructions at nearly their solo rate.  The workgroup is therefore two groups of four wavefronts
 // (wavefront w and w + 4 share a SIMD), each group owning 128 query rows, that alternate between
-//   M(t): the matrix phase  -- O^T += V^T P^T of tile t-1, then S^T = K Q^T of tile t (32 MFMAs), and
+//   M(t): the matrix phase  -- O^T += V^T P^T of tile t-1, then S^T = K Q^T of tile t (D / 4 MFMAs), and
 //   V(t): the vector phase  -- softmax numerators of tile t, P rounded to bf16 operand slots,
 // one workgroup barrier per phase, group 1 running one phase behind group 0, so that every SIMD always
 // has one wavefront in a matrix phase and one in a vector phase.  The vector-phase group also issues the
@@ -31,20 +31,26 @@
 
 namespace {
 
-constexpr int D = 128;
 constexpr int TN = 64;             // keys per tile
 constexpr int NB = 4;              // LDS buffers per tensor
 constexpr int GROUP_ROWS = 128;    // q rows per wavefront group (32 per wavefront)
 constexpr int WG_ROWS = 256;       // q rows per workgroup
 // LDS rows are padded instead of swizzled, so that every operand fragment sits at (one per-lane base
-// register) + (compile-time offset): K rows take 272 bytes (16 consecutive rows then spread over all 64
-// banks for the 128-bit row reads), V rows 320 bytes (the 4 rows x 64 bytes of a transposed 64-bit read
-// then spread over all 64 banks).
-constexpr int K_ROW_BYTES = 272, V_ROW_BYTES = 320;
-constexpr int K_TILE_BYTES = TN * K_ROW_BYTES;   // 17 KB = 17 wave-wide 1 KB transfers
-constexpr int V_TILE_BYTES = TN * V_ROW_BYTES;   // 20 KB = 20 transfers
-constexpr int DMA_PER_WAVE = 5;                  // most transfers a wavefront issues per tile (K: 17 transfers, V: 20, over 4 wavefronts)
-constexpr int O_STAGE_STRIDE = D + 4;   // floats per staged output row (epilogue)
+// register) + (compile-time offset): K rows take 2 D + 16 bytes (272 or 144: 16 consecutive rows then spread
+// over all 64 banks for the 128-bit row reads), V rows 2 D + 64 bytes (320 or 192: the 4 rows x 64 bytes of a
+// transposed 64-bit read then spread over all 64 banks).  Tiles are whole numbers of wave-wide 1 KB transfers:
+// K 17 (D = 128) or 9 (D = 64), V 20 or 12.
+template <int D> struct FwdCfg {
+    static_assert(D == 64 || D == 128, "head_dim 64 or 128");
+    static constexpr int NKS = D / 16;     // 16-wide contraction steps across the head dimension
+    static constexpr int NDB = D / 32;     // 32-column blocks of the output
+    static constexpr int K_ROW_BYTES = 2 * D + 16, V_ROW_BYTES = 2 * D + 64;
+    static constexpr int K_TILE_BYTES = TN * K_ROW_BYTES, V_TILE_BYTES = TN * V_ROW_BYTES;
+    static constexpr int DMA_PER_WAVE = (V_TILE_BYTES / 1024 + 3) / 4;   // most transfers a wavefront issues per tile (5 or 3)
+    static constexpr int O_STAGE_STRIDE = D + 4;   // floats per staged output row (epilogue)
+    static_assert(K_TILE_BYTES % 1024 == 0 && V_TILE_BYTES % 1024 == 0, "tiles are whole transfers");
+    static_assert((K_TILE_BYTES / 1024 + 3) / 4 == DMA_PER_WAVE, "K and V wavefronts issue the same maximum");
+};
 constexpr int K_AHEAD = 4;         // group 1 fetches K(t + 4) during V(t)
 constexpr int V_AHEAD = 2;         // group 0 fetches V(t + 2) during V(t)
 constexpr float LOG2E = 1.4426950408889634f;
@@ -56,18 +62,23 @@ constexpr float SUM_HI = 1.1529215e18f;    // 2^60
 
 __device__ __forceinline__ int swz_row(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
 
-struct FwdSmem {
-    unsigned char k[NB][K_TILE_BYTES];   // 4 x 17 KB
-    unsigned char v[NB][V_TILE_BYTES];   // 4 x 20 KB
+template <int D> struct FwdSmem {
+    unsigned char k[NB][FwdCfg<D>::K_TILE_BYTES];   // 4 x 17 KB (D = 128)
+    unsigned char v[NB][FwdCfg<D>::V_TILE_BYTES];   // 4 x 20 KB
     int kpos[2 * NB][TN];     // key positions of the tiles that need a mask, written K_AHEAD tiles ahead
-    // the epilogue stages 8 x (32 x 132 + 32) floats over the start of this struct
+    // the epilogue stages 8 x (32 x (D + 4) + 32) floats over the start of this struct
 };
-static_assert(sizeof(FwdSmem) >= 8 * (32 * O_STAGE_STRIDE + 32) * 4, "epilogue staging does not fit");
 
+template <int D>
 __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const int n_q_tiles)
 {
+    using C = FwdCfg<D>;
+    constexpr int NKS = C::NKS, NDB = C::NDB, K_ROW_BYTES = C::K_ROW_BYTES, V_ROW_BYTES = C::V_ROW_BYTES;
+    constexpr int K_TILE_BYTES = C::K_TILE_BYTES, V_TILE_BYTES = C::V_TILE_BYTES, DMA_PER_WAVE = C::DMA_PER_WAVE;
+    constexpr int O_STAGE_STRIDE = C::O_STAGE_STRIDE;
+    static_assert(sizeof(FwdSmem<D>) >= 8 * (32 * O_STAGE_STRIDE + 32) * 4, "epilogue staging does not fit");
     const AttnGeom& g = a.g;
-    __shared__ __attribute__((aligned(1024))) FwdSmem sm;
+    __shared__ __attribute__((aligned(1024))) FwdSmem<D> sm;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -113,20 +124,20 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
     if (NT == 0 && a.accumulate) return;
 
     // Q^T operand fragments: lane (row l32, half hh) holds d = 16*ks + 8*hh .. +7
-    bf16x8 qf[8];
+    bf16x8 qf[NKS];
     {
         const uint16_t* qp = q + (long long)my_row_c * g.q_stride_tok + (long long)h * g.q_stride_head + 8 * hh;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+        for (int ks = 0; ks < NKS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) pin(qf[ks]);
+        for (int ks = 0; ks < NKS; ++ks) pin(qf[ks]);
     }
 
     // Direct global->LDS fetch of one tile by the four wavefronts of a group.  A transfer is one wave-wide
     // instruction: lane L writes the 16 bytes at (transfer * 1024 + 16 * L) of the tile's LDS image and reads
     // them from wherever the kernel points it, here the 16-byte piece of the key row that belongs there (pad
     // pieces re-read piece 0).  Wavefront wg issues the transfers wg, wg + 4, ... below the tile's transfer
-    // count (5 or 4 of them).
+    // count (at most DMA_PER_WAVE of them).
     const int row_bytes = grp ? K_ROW_BYTES : V_ROW_BYTES;
     const int n_xfer = grp ? K_TILE_BYTES / 1024 : V_TILE_BYTES / 1024;
     // transfers this wavefront issues per tile: its share wg, wg + 4, ... of the tile's n_xfer (4 or 5)
@@ -138,7 +149,7 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
         const int pos = (wg + 4 * i) * 1024 + 16 * lane;
         int r = pos / row_bytes, c = (pos - r * row_bytes) >> 4;
         if (wg + 4 * i >= n_xfer) r = 0;
-        if (c >= 16) c = 0;
+        if (c >= D / 8) c = 0;
         fetch_row[i] = r;
         fetch_off[i] = 2u * (uint32_t)(r * (int)g.kv_stride_tok + c * 8);
     }
@@ -183,15 +194,16 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
     v_addr[0] = lds_v + (4 * hh + jj) * V_ROW_BYTES + 2 * (16 * grp2 + 4 * (j16 & 3));
     v_addr[1] = v_addr[0] + 2 * V_TILE_BYTES;
 
-    f32x16 oacc[4];
+    f32x16 oacc[NDB];
     f32x16 s[2];
     bf16x8 pf[4];
     float m_run, l_run, lr_run, thr_raw;
     const float c_log2 = g.scale * LOG2E, inv_c_log2 = 1.0f / c_log2;
 
-    // Matrix phase on buffers (B + NB - 1) % NB (V of tile t-1) and B (K of tile t).  Steps 0..15:
-    // O^T[d][q] += V^T P^T, four 16-key steps x four 32-column blocks; steps 16..31: S^T[key][q] for two
+    // Matrix phase on buffers (B + NB - 1) % NB (V of tile t-1) and B (K of tile t).  Steps 0..NPV-1:
+    // O^T[d][q] += V^T P^T, four 16-key steps x NDB 32-column blocks; steps NPV..NST-1: S^T[key][q] for two
     // 32-key blocks.  [FIRST, LAST) selects the steps; operand fragments are requested PF steps ahead.
+    constexpr int NPV = 4 * NDB, NST = NPV + 2 * NKS;
     auto m_phase = [&](auto bc, auto first_c, auto last_c) __attribute__((always_inline)) {
         constexpr int B = decltype(bc)::value, FIRST = decltype(first_c)::value, LAST = decltype(last_c)::value;
         constexpr int PF = 4;
@@ -202,12 +214,12 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
         bf16x8 kb[NS];
         auto issue = [&](auto stc) __attribute__((always_inline)) {
             constexpr int st = decltype(stc)::value, slot = (st - FIRST) % NS;
-            if constexpr (st < 16) {
-                constexpr int u = st >> 2, db = st & 3;
+            if constexpr (st < NPV) {
+                constexpr int u = st / NDB, db = st % NDB;
                 lds_issue_tr16<VOFF + 16 * u * V_ROW_BYTES + 64 * db>(ta[slot], v_addr[BV / 2]);
                 lds_issue_tr16<VOFF + (16 * u + 8) * V_ROW_BYTES + 64 * db>(tb[slot], v_addr[BV / 2]);
             } else {
-                constexpr int b = (st - 16) & 1, ks = (st - 16) >> 1;
+                constexpr int b = (st - NPV) & 1, ks = (st - NPV) >> 1;
                 lds_issue_b128<KOFF + 32 * b * K_ROW_BYTES + 32 * ks>(kb[slot], k_addr);
             }
         };
@@ -216,13 +228,13 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
             if constexpr (st + PF < LAST) issue(IC<st + PF>{});
             // LDS reads younger than this step's fragment: those of the next PF steps that exist
             constexpr int hi = st + PF < LAST ? st + PF : LAST - 1;
-            constexpr int n_tr = (hi < 16 ? hi : 15) - (st < 16 ? st : 15);      // steps in (st, hi] below 16
+            constexpr int n_tr = (hi < NPV ? hi : NPV - 1) - (st < NPV ? st : NPV - 1);      // steps in (st, hi] below NPV
             constexpr int younger = 2 * n_tr + ((hi - st) - n_tr);
-            if constexpr (st < 16) {
+            if constexpr (st < NPV) {
                 lds_wait<younger>(ta[slot], tb[slot]);
-                oacc[st & 3] = mfma32(join_halves(ta[slot], tb[slot]), pf[st >> 2], oacc[st & 3]);
+                oacc[st % NDB] = mfma32(join_halves(ta[slot], tb[slot]), pf[st / NDB], oacc[st % NDB]);
             } else {
-                constexpr int b = (st - 16) & 1, ks = (st - 16) >> 1;
+                constexpr int b = (st - NPV) & 1, ks = (st - NPV) >> 1;
                 lds_wait<younger>(kb[slot]);
                 const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
                 s[b] = mfma32(kb[slot], qf[ks], ks == 0 ? zero : s[b]);
@@ -275,7 +287,7 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
                     // (one multiply per register through inline assembly: written as vector arithmetic the
                     // compiler splats alpha into 16 extra registers, which costs the hot loop a spill)
 #pragma unroll
-                    for (int db = 0; db < 4; ++db)
+                    for (int db = 0; db < NDB; ++db)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) asm("v_mul_f32 %0, %1, %0" : "+v"(oacc[db][r]) : "v"(alpha));
                     m_run = m_new;
@@ -309,7 +321,7 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
     // flow is the same everywhere.
     auto run = [&](const bool exact) __attribute__((always_inline)) {
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
         m_run = NEG_BIG; l_run = 0.f; lr_run = 0.f;
@@ -321,18 +333,18 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
             for (int j = 0; j < n_pre && j < NT; ++j) fetch_tile(j);
         }
         if (grp == 1) {   // K(0) complete before anyone's M(0)
-            wait_tiles_in_flight((NT < K_AHEAD ? NT : K_AHEAD) - 1, my_xfers);
+            wait_tiles_in_flight<DMA_PER_WAVE>((NT < K_AHEAD ? NT : K_AHEAD) - 1, my_xfers);
             wg_barrier();
         }
         // before M(t): group 0 has requested V up to min(t + 1, NT - 1) and needs V(t - 1) complete
         auto enter_m = [&](int t) __attribute__((always_inline)) {
-            if (grp == 0) wait_tiles_in_flight(NT - t < 2 ? NT - t : 2, my_xfers);
+            if (grp == 0) wait_tiles_in_flight<DMA_PER_WAVE>(NT - t < 2 ? NT - t : 2, my_xfers);
             wg_barrier();
         };
         // before V(t): group 1 has requested K up to min(t + 3, NT - 1) and needs K(t + 1) complete; then the
         // vector phase itself, starting with this group's share of the fetches
         auto vector_part = [&](int t, auto first_c) __attribute__((always_inline)) {
-            if (grp == 1 && t + 1 < NT) wait_tiles_in_flight(NT - 2 - t < 2 ? NT - 2 - t : 2, my_xfers);
+            if (grp == 1 && t + 1 < NT) wait_tiles_in_flight<DMA_PER_WAVE>(NT - 2 - t < 2 ? NT - 2 - t : 2, my_xfers);
             wg_barrier();
             const int j = t + (grp ? K_AHEAD : V_AHEAD);
             if (j < NT) fetch_tile(j);
@@ -340,33 +352,33 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
             else v_phase(t & (2 * NB - 1), first_c, std::false_type{}, exact);
         };
         enter_m(0);
-        m_phase(IC<0>{}, IC<16>{}, IC<32>{});
+        m_phase(IC<0>{}, IC<NPV>{}, IC<NST>{});
         vector_part(0, std::true_type{});
         // tiles 1 .. NT-1: four at a time in a straight line (buffer = t % 4 is then a compile-time constant and
         // no accumulator passes through a control-flow merge), then the remaining ones through a switch
         int t = 1;
         for (; t + 3 < NT; t += 4) {
-            enter_m(t);     m_phase(IC<1>{}, IC<0>{}, IC<32>{}); vector_part(t, std::false_type{});
-            enter_m(t + 1); m_phase(IC<2>{}, IC<0>{}, IC<32>{}); vector_part(t + 1, std::false_type{});
-            enter_m(t + 2); m_phase(IC<3>{}, IC<0>{}, IC<32>{}); vector_part(t + 2, std::false_type{});
-            enter_m(t + 3); m_phase(IC<0>{}, IC<0>{}, IC<32>{}); vector_part(t + 3, std::false_type{});
+            enter_m(t);     m_phase(IC<1>{}, IC<0>{}, IC<NST>{}); vector_part(t, std::false_type{});
+            enter_m(t + 1); m_phase(IC<2>{}, IC<0>{}, IC<NST>{}); vector_part(t + 1, std::false_type{});
+            enter_m(t + 2); m_phase(IC<3>{}, IC<0>{}, IC<NST>{}); vector_part(t + 2, std::false_type{});
+            enter_m(t + 3); m_phase(IC<0>{}, IC<0>{}, IC<NST>{}); vector_part(t + 3, std::false_type{});
         }
         for (; t < NT; ++t) {
             enter_m(t);
             switch (t & 3) {
-                case 0: m_phase(IC<0>{}, IC<0>{}, IC<32>{}); break;
-                case 1: m_phase(IC<1>{}, IC<0>{}, IC<32>{}); break;
-                case 2: m_phase(IC<2>{}, IC<0>{}, IC<32>{}); break;
-                default: m_phase(IC<3>{}, IC<0>{}, IC<32>{}); break;
+                case 0: m_phase(IC<0>{}, IC<0>{}, IC<NST>{}); break;
+                case 1: m_phase(IC<1>{}, IC<0>{}, IC<NST>{}); break;
+                case 2: m_phase(IC<2>{}, IC<0>{}, IC<NST>{}); break;
+                default: m_phase(IC<3>{}, IC<0>{}, IC<NST>{}); break;
             }
             vector_part(t, std::false_type{});
         }
         enter_m(NT);
         switch (NT & 3) {
-            case 0: m_phase(IC<0>{}, IC<0>{}, IC<16>{}); break;
-            case 1: m_phase(IC<1>{}, IC<0>{}, IC<16>{}); break;
-            case 2: m_phase(IC<2>{}, IC<0>{}, IC<16>{}); break;
-            default: m_phase(IC<3>{}, IC<0>{}, IC<16>{}); break;
+            case 0: m_phase(IC<0>{}, IC<0>{}, IC<NPV>{}); break;
+            case 1: m_phase(IC<1>{}, IC<0>{}, IC<NPV>{}); break;
+            case 2: m_phase(IC<2>{}, IC<0>{}, IC<NPV>{}); break;
+            default: m_phase(IC<3>{}, IC<0>{}, IC<NPV>{}); break;
         }
         if (grp == 0) wg_barrier();
     };
@@ -383,8 +395,8 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
     }
 
     // Epilogue.  Every lane scales its row's O^T registers and merges the LSE; the scaled rows go through
-    // LDS (free now; a private 32 x 132-float region per wavefront, padded against bank conflicts) so that
-    // the global accesses are row-contiguous: one instruction covers two whole 512-byte rows of o.
+    // LDS (free now; a private 32 x (D + 4)-float region per wavefront, padded against bank conflicts) so that
+    // the global accesses are row-contiguous: one instruction covers 1 KB of whole rows of o (two at D = 128).
     float inv = 0.f, lse_new = -INFINITY;
     if (l_tot > 0.f) {
         inv = lr_tot > 0.f ? 1.0f / lr_tot : 0.f;
@@ -406,7 +418,7 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
     float* stage = reinterpret_cast<float*>(&sm) + wave * (32 * O_STAGE_STRIDE + 32);
     float* stage_wa = stage + 32 * O_STAGE_STRIDE;
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int b = 0; b < 4; ++b)
             *reinterpret_cast<float4*>(&stage[l32 * O_STAGE_STRIDE + 32 * db + 8 * b + 4 * hh]) =
@@ -419,21 +431,24 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // lane -> (row within a group of ROWS_PER_INST rows, 16-byte piece of the row)
+    constexpr int LANES_PER_ROW = D / 4, ROWS_PER_INST = 64 / LANES_PER_ROW, N_INST = 32 / ROWS_PER_INST;
+    const int sub_row = lane / LANES_PER_ROW, piece = lane % LANES_PER_ROW;
     const int wrow0 = grow0 + 32 * wg;
-    float* obase = a.o + ((long long)wrow0 * g.nq + h) * D + 4 * l32;
+    float* obase = a.o + ((long long)wrow0 * g.nq + h) * D + 4 * piece;
     const long long row_stride = (long long)g.nq * D;
-    float4 val[16];
-    float4 old[16];
+    float4 val[N_INST];
+    float4 old[N_INST];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int r = 2 * i + hh;
-        val[i] = *reinterpret_cast<const float4*>(&stage[r * O_STAGE_STRIDE + 4 * l32]);
+    for (int i = 0; i < N_INST; ++i) {
+        const int r = ROWS_PER_INST * i + sub_row;
+        val[i] = *reinterpret_cast<const float4*>(&stage[r * O_STAGE_STRIDE + 4 * piece]);
         if (a.accumulate && wrow0 + r < g.lq) old[i] = *reinterpret_cast<const float4*>(obase + r * row_stride);
         else old[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int r = 2 * i + hh;
+    for (int i = 0; i < N_INST; ++i) {
+        const int r = ROWS_PER_INST * i + sub_row;
         const float w = stage_wa[r];
         float4 o4 = val[i];
         o4.x += w * old[i].x; o4.y += w * old[i].y; o4.z += w * old[i].z; o4.w += w * old[i].w;
@@ -446,6 +461,9 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
 hipError_t hexi_launch_fwd_bf16(const FwdArgs& a, hipStream_t s)
 {
     const int n_q_tiles = (a.g.lq + WG_ROWS - 1) / WG_ROWS;
-    fwd_bf16_kernel<<<(unsigned)(a.g.nq * n_q_tiles), 512, 0, s>>>(a, n_q_tiles);
+    const unsigned grid = (unsigned)(a.g.nq * n_q_tiles);
+    if (a.g.d == 128) fwd_bf16_kernel<128><<<grid, 512, 0, s>>>(a, n_q_tiles);
+    else if (a.g.d == 64) fwd_bf16_kernel<64><<<grid, 512, 0, s>>>(a, n_q_tiles);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }

@@ -191,24 +191,23 @@ template <int FIRST, int LAST, class F> __device__ __forceinline__ void for_rang
     for_range_impl<FIRST>(std::make_integer_sequence<int, LAST - FIRST>{}, f);
 }
 
-// Tiles are fetched with 5 wave-wide global->LDS transfers per wavefront per tile; transfers complete in
-// order, so "at most `allowed_tiles` younger tiles still in flight" is a vmcnt of 5 per tile.
-__device__ __forceinline__ void wait_tiles_in_flight(int allowed_tiles)
+// Tiles are fetched with wave-wide global->LDS transfers, PER_TILE of them per wavefront per tile; transfers
+// complete in order, so "at most `allowed_tiles` younger tiles still in flight" is a vmcnt of PER_TILE per tile.
+template <int PER_TILE> __device__ __forceinline__ void wait_tiles_in_flight_n(int allowed_tiles)
 {
-    if (allowed_tiles >= 3) asm volatile("s_waitcnt vmcnt(15)" ::: "memory");
-    else if (allowed_tiles == 2) asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
-    else if (allowed_tiles == 1) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+    static_assert(3 * PER_TILE < 64, "vmcnt holds 6 bits");
+    if (allowed_tiles >= 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * PER_TILE) : "memory");
+    else if (allowed_tiles == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * PER_TILE) : "memory");
+    else if (allowed_tiles == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PER_TILE) : "memory");
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
-// Same for a wavefront that issues `per_tile` (4 or 5, wave-uniform) transfers per tile.
-__device__ __forceinline__ void wait_tiles_in_flight(int allowed_tiles, int per_tile)
+// Same for a wavefront that issues `per_tile` transfers per tile, where per_tile (wave-uniform) is MOST or
+// MOST - 1: the four wavefronts of a group share a tile's transfers round-robin.
+template <int MOST> __device__ __forceinline__ void wait_tiles_in_flight(int allowed_tiles, int per_tile)
 {
-    if (per_tile == 5) wait_tiles_in_flight(allowed_tiles);
-    else if (allowed_tiles >= 3) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
-    else if (allowed_tiles == 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-    else if (allowed_tiles == 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (per_tile == MOST) wait_tiles_in_flight_n<MOST>(allowed_tiles);
+    else wait_tiles_in_flight_n<MOST - 1>(allowed_tiles);
 }
 
 // Workgroup barrier that the compiler's scheduler does not move code across.
@@ -219,12 +218,14 @@ __device__ __forceinline__ void wg_barrier()
     __builtin_amdgcn_sched_barrier(0);
 }
 
-// LDS tile layout of the kernels that read a [64 rows][128 bf16] tile both row-wise (128-bit reads, 32
-// consecutive rows across the lanes) and transposed (ds_read_b64_tr_b16, 4 consecutive rows per 16-lane
-// group): rows are 272 bytes apart (256 + 16 of padding) and stored in the order p16_row(), which swaps
-// the two 2-bit digits of the row index inside every block of 16 rows.  Consecutive rows r..r+3 then sit 4
-// LDS rows (= 16 banks) apart, so both access patterns touch all 64 banks exactly once, and every operand
-// fragment is at (one per-lane base register) + (a compile-time offset).
-constexpr int P16_ROW_BYTES = 272;
-constexpr int P16_TILE_BYTES = 64 * P16_ROW_BYTES;   // 17 KB = 17 wave-wide 1 KB transfers
+// LDS tile layout of the kernels that read a [64 rows][D bf16] tile (D = 64 or 128) both row-wise (128-bit
+// reads, 32 consecutive rows across the lanes) and transposed (ds_read_b64_tr_b16, 4 consecutive rows per
+// 16-lane group): rows are 2 D + 16 bytes apart (16 of padding: 68 or 36 dwords, so that 16 consecutive LDS
+// rows start 4 banks apart and every fourth one 16 banks apart) and stored in the order p16_row(), which
+// swaps the two 2-bit digits of the row index inside every block of 16 rows.  Consecutive rows r..r+3 then
+// sit 4 LDS rows (= 16 banks) apart, so both access patterns touch all 64 banks exactly once, and every
+// operand fragment is at (one per-lane base register) + (a compile-time offset).  A tile is a whole number of
+// wave-wide 1 KB transfers: 17 (D = 128) or 9 (D = 64).
+__host__ __device__ constexpr int p16_row_bytes(int d) { return 2 * d + 16; }
+__host__ __device__ constexpr int p16_tile_bytes(int d) { return 64 * p16_row_bytes(d); }
 __host__ __device__ constexpr int p16_row(int r) { return (r & ~15) | ((r & 3) << 2) | ((r >> 2) & 3); }

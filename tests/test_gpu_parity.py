@@ -93,7 +93,7 @@ def _custom(name, dtype, nq, nkv, d, l_tot, q_segs, chunks, kv_of_q=None, k_scal
     return wl.Workload(name, dtype, nq, nkv, d, l_tot, q_segs, chunks, k_scale=k_scale, kv_of_q=kv_of_q)
 
 
-@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64), ("f32", 128)])
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 64), ("f32", 128)])
 def test_ragged_lengths_and_many_segments(dtype, d):
     # unaligned shard / chunk lengths (1000, 777, 1, 130), a shard of 4 segments, chunks of 1-3
     # segments, one chunk wholly in the future, rows that see nothing of some chunk
@@ -127,11 +127,11 @@ def test_dkdv_head_runs(run_len, monkeypatch):
     _run_and_compare(w, seed=22, fused=False)
 
 
-def _random_case(rng, i, l_range=(200, 1400), max_heads=8):
+def _random_case(rng, i, l_range=(200, 1400), max_heads=8, d_bf16=128):
     """A seeded random shard: the sequence [0, L) cut into pieces, each piece dealt to one of 1-4 chunks, the q
     shard takes 1-3 pieces; random head counts and kv map."""
     dtype = "bf16" if i % 3 else "f32"
-    d = 128 if dtype == "bf16" else int(rng.choice([64, 128]))
+    d = d_bf16 if dtype == "bf16" else int(rng.choice([64, 128]))
     L = int(rng.integers(*l_range))
     n_pieces = int(rng.integers(2, 9))
     cuts = sorted(set(int(c) for c in rng.integers(1, L, size=n_pieces - 1)))
@@ -165,6 +165,36 @@ def test_randomized_longer_shards():
     for i in range(8):
         w = _random_case(rng, 3 * i + 1, l_range=(2500, 6000), max_heads=4)     # bf16 cases
         _run_and_compare(w, seed=200 + i, fused=bool(i % 2))
+
+
+def test_bf16_head_dim_64_minis_and_head_runs(monkeypatch):
+    # the bf16 kernels at head_dim 64 (the smaller models' heads): configurations 2 and 5 shrunk, heads halved to
+    # 64 columns (zigzag pairs, one GQA group of 8, FULL + diagonal + EMPTY chunks), fused and unfused
+    import dataclasses
+    for idx, shrink in ((2, 32), (5, 64)):
+        w = dataclasses.replace(wl.config(idx, shrink=shrink), head_dim=64, name=f"cfg{idx}_mini_d64")
+        _run_and_compare(w, fused=(idx == 2))
+    # forced dK/dV head runs: whole groups, runs with a remainder, non-adjacent heads of a group
+    for run_len in (1, 3, 8):
+        monkeypatch.setenv("HEXI_DKDV_RUN_LEN", str(run_len))
+        w = _custom(f"runs{run_len}_d64", "bf16", 8, 3, 64, 700, [(150, 70), (400, 300)], [[(0, 333)], [(333, 367)]],
+                    kv_of_q=[0, 1, 0, 0, 2, 0, 1, 0])
+        _run_and_compare(w, seed=31)
+
+
+def test_bf16_head_dim_64_randomized_shards():
+    rng = np.random.default_rng(64)
+    for i in range(12):
+        long_case = i >= 8     # the last four span many tiles per workgroup
+        w = _random_case(rng, 3 * i + 1, l_range=(2500, 6000) if long_case else (200, 1400),
+                         max_heads=4 if long_case else 8, d_bf16=64)
+        _run_and_compare(w, seed=300 + i, fused=bool(i % 2))
+
+
+@pytest.mark.parametrize("lq,lc", [(1, 1), (63, 65), (256, 129), (257, 300), (513, 1)])
+def test_bf16_head_dim_64_workgroup_boundary_sizes(lq, lc):
+    w = _custom(f"edge64_{lq}_{lc}", "bf16", 2, 1, 64, lc + lq, [(lc, lq)], [[(0, lc)], [(lc, lq)]])
+    _run_and_compare(w, seed=lq * 1000 + lc + 64)
 
 
 @pytest.mark.parametrize("run_len", [0, 1, 2])
