@@ -284,12 +284,10 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
                     const float alpha = fast_exp2(m_run - m_new);
                     l_run *= alpha;
                     lr_run *= alpha;
-                    // (one multiply per register through inline assembly: written as vector arithmetic the
-                    // compiler splats alpha into 16 extra registers, which costs the hot loop a spill)
 #pragma unroll
                     for (int db = 0; db < NDB; ++db)
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) asm("v_mul_f32 %0, %1, %0" : "+v"(oacc[db][r]) : "v"(alpha));
+                        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
                     m_run = m_new;
                     thr_raw = (m_run + RESCALE_SLACK) * inv_c_log2;
                 }
@@ -319,7 +317,10 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
     // barrier before every phase; group 1 starts one barrier late and group 0 ends with one extra.  Both
     // groups walk all NT tiles (a group whose rows see fewer tiles masks the rest away), so the control
     // flow is the same everywhere.
-    auto run = [&](const bool exact) __attribute__((always_inline)) {
+    // (The softmax variant is a compile-time parameter: with a run-time flag the compiler keeps both variants'
+    // state alive through the tile loop, which cost the fast path 3 %.)
+    auto run = [&](auto exact_c) __attribute__((always_inline)) {
+        constexpr bool exact = decltype(exact_c)::value;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -383,15 +384,17 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
         if (grp == 0) wg_barrier();
     };
 
-    float l_tot, lr_tot;
-    for (int pass = 0; pass < 2; ++pass) {   // pass 1 (exact online softmax) only if a row of pass 0 left the safe range
-        run(pass == 1);
-        l_tot = sum_across_halves(l_run);
-        lr_tot = sum_across_halves(lr_run);
+    run(std::false_type{});
+    float l_tot = sum_across_halves(l_run), lr_tot = sum_across_halves(lr_run);
+    {
         // a row that sees any key of the chunk sees its first key
         const bool sees = my_row < g.lq && my_pos >= g.ks.start[0];
-        const int bad = pass == 0 && sees && !(l_tot >= SUM_LO && l_tot <= SUM_HI);
-        if (!__syncthreads_or(bad)) break;
+        const int bad = sees && !(l_tot >= SUM_LO && l_tot <= SUM_HI);
+        if (__syncthreads_or(bad)) {   // a row left the safe range: repeat the tiles with the exact online softmax
+            run(std::true_type{});
+            l_tot = sum_across_halves(l_run);
+            lr_tot = sum_across_halves(lr_run);
+        }
     }
 
     // Epilogue.  Every lane scales its row's O^T registers and merges the LSE; the scaled rows go through

@@ -333,7 +333,8 @@ def test_workgroup_boundary_sizes(lq, lc):
     _run_and_compare(w, seed=lq * 1000 + lc)
 
 
-def test_forward_exact_softmax_fallback():
+@pytest.mark.parametrize("d", [128, 64])
+def test_forward_exact_softmax_fallback(d):
     # The fast forward path fixes each row's softmax reference after its first key tile and repeats the
     # workgroup with the exact online softmax when a row's sum leaves [2^-60, 2^60].  Keys beyond the first
     # tile are scaled so that later scores exceed the first tile's maximum by far more than 2^100 (rows 0-255,
@@ -341,7 +342,7 @@ def test_forward_exact_softmax_fallback():
     # is harmless but must stay exact too).  Everything is compared with the oracle.
     dev = torch.device(DEV)
     g = torch.Generator().manual_seed(99)
-    lq, lc, nq, d = 300, 640, 2, 128
+    lq, lc, nq = 300, 640, 2
     for first_scale, later_scale in ((1.0, 60.0), (60.0, 0.02)):
         q = (torch.randn((lq, nq, d), generator=g) * 3).to(torch.bfloat16)
         k = torch.randn((lc, 1, d), generator=g)
