@@ -398,7 +398,7 @@ hipError_t hexi_launch_bwd_bf16(const BwdArgs& a, hipStream_t s)
         }
         for (int kh = 0; kh < a.g.nkv; ++kh) unused |= (cnt[kh] == 0);   // a kv head no local q head reads: zero gradient
         // Run length: the longest divisor of the largest group's size (so that its runs are equally long) for which
-        // the launch still has about three workgroups per CU and a workgroup walks at most 768 q tiles.  A run
+        // the launch still has about three workgroups per CU and a workgroup walks at most 512 q tiles.  A run
         // amortises the workgroup's prologue and epilogue (about 20 tiles' worth) and, when it covers the whole
         // group, needs no atomics; but the workgroups of an XCD stream the same Q / dO tiles only while they stay
         // in step, and long tile sequences let them drift apart (measured: more L2 misses, slower launches).
@@ -411,7 +411,7 @@ hipError_t hexi_launch_bwd_bf16(const BwdArgs& a, hipStream_t s)
         const int n_qtiles = (a.g.lq + TM - 1) / TM;
         const int max_tiles = a.g.lc > 0 ? n_qtiles - seg_rows_le(a.g.qs, seg_pos_of_row(a.g.ks, 0) - 1) / TM : 0;
         int run_len = max_cnt;
-        while (run_len > 1 && (max_cnt % run_len != 0 || (long long)run_len * max_tiles > 768 ||
+        while (run_len > 1 && (max_cnt % run_len != 0 || (long long)run_len * max_tiles > 512 ||
                                (long long)n_runs_for(run_len) * n_kv_tiles < 3 * 256))
             --run_len;
         if (const char* forced = getenv("HEXI_DKDV_RUN_LEN")) {     // tuning / test override of the heuristic
