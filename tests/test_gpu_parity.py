@@ -382,3 +382,26 @@ def test_device_share_of_a_scheduled_plan():
         w = wl.from_schedule(plan["groups"], plan["l_group"], plan["n_heads"], dev, head_dim=128, q_per_kv=2)
         assert w.n_q_heads == plan["n_heads"][dev] and len(w.chunks) == 2
         _run_and_compare(w, seed=31 + dev)
+
+
+def test_measured_compute_rate_feeds_the_scheduler():
+    # c_d of the cost model (Eq. 11 convention: 16 * Lq * Lc * n_d * d_h flop per fully visible step) measured on
+    # this GPU through the library's own kernels, then used as the compute rate of a homogeneous 8-device plan
+    import sys, os
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+    from sched_util import cluster_arrays, model_args
+    from paper_2605_07569_amd import calibrate
+    c_d = calibrate.measure_c_d(lq=4096, lc=4096, reps=3)
+    print(f"\n  measured c_d = {c_d / 1e12:.0f} TFLOP/s (Eq. 11 convention)", flush=True)
+    # 14/16 of it is the counted rate on unmasked pairs: between a tenth of and the whole bf16 MFMA roof
+    assert 0.25e15 < c_d < 2.9e15
+    arr = cluster_arrays([("h100", 8)])
+    arr["c"] = np.full(8, c_d)
+    model = model_args(l_tot=65536, n_heads=32, hidden=4096)
+    plan = hexi.hexi_sched_solve(arr, model, m2=4, i_max=10)
+    assert sum(plan["l_group"]) == 65536 and all(sum(plan["n_heads"][d] for d in g) == 32 for g in plan["groups"])
+    t_blk, t_non, t_a2a, t_ring, feasible = hexi.hexi_sched_cost(arr, model, plan["groups"], plan["l_group"], plan["s_pre"], plan["n_heads"])
+    assert feasible and abs(t_blk - plan["cost"]) <= 1e-12 * t_blk
+    # a slower device rate can only raise the modelled ring time
+    arr_slow = dict(arr, c=np.full(8, c_d / 4))
+    assert hexi.hexi_sched_cost(arr_slow, model, plan["groups"], plan["l_group"], plan["s_pre"], plan["n_heads"])[3] >= t_ring
