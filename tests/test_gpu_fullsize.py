@@ -1,4 +1,5 @@
-"""Full-size parity: configurations 2-5 at their real sizes, in the launch configuration bench.py times.
+"""Full-size parity: configurations 2-5 at their real sizes (and configuration 2 with 64-column heads), in the
+launch configuration bench.py times.
 
 The oracle cannot recompute a whole full-size shard, so:
   (i)  o, lse and dq are row-local: sampled rows (first / last rows of every segment, rows around tile
@@ -39,9 +40,12 @@ def _sample_rows(w, n_target):
     return np.array(sorted(rows), dtype=np.int64)
 
 
-@pytest.mark.parametrize("idx", [2, 3, 4, 5])
-def test_full_size_sampled_rows_subshard_and_properties(idx):
+@pytest.mark.parametrize("idx,head_dim", [(2, 128), (3, 128), (4, 128), (5, 128), (2, 64)])
+def test_full_size_sampled_rows_subshard_and_properties(idx, head_dim):
     w = wl.config(idx)
+    if head_dim != w.head_dim:      # variant: the same shard with 64-column heads (the launch `bench.py --head-dim 64` times)
+        import dataclasses
+        w = dataclasses.replace(w, head_dim=head_dim, name=f"{w.name}_d{head_dim}")
     print(f"\n[{w.name}] generating inputs", flush=True)
     inputs = wl.make_inputs(w)
     q_pos_all = wl.seg_positions(w.q_segs).numpy()
