@@ -43,6 +43,8 @@ extern "C" {
 #define HEXI_EHIP         (-5)  /* the HIP runtime refused a launch */
 #define HEXI_EINFEASIBLE   (-6)  /* hexi_sched_solve: no candidate schedule fits the devices' memory */
 
+#define HEXI_MAX_TOKEN_STRIDE (1 << 22)  /* elements; larger token strides are HEXI_EUNSUPPORTED */
+
 #define HEXI_BF16 0
 #define HEXI_F32  1
 
@@ -75,7 +77,7 @@ typedef struct {
     const int32_t* kv_of_q;     /* HOST [n_q_heads]: local kv head read by each local q head;
                                    NULL => h / (n_q_heads / n_kv_heads) */
     float   softmax_scale;      /* e.g. 1/sqrt(head_dim) */
-    int64_t q_stride_tok, q_stride_head;    /* strides of q and d_o, in elements */
+    int64_t q_stride_tok, q_stride_head;    /* strides of q and d_o, in elements; token strides <= HEXI_MAX_TOKEN_STRIDE */
     int64_t kv_stride_tok, kv_stride_head;  /* strides of k and v, in elements */
 } hexi_attn_desc;
 

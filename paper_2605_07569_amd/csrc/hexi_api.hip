@@ -124,6 +124,9 @@ static int build_geom(const hexi_attn_desc* d, const hexi_range* q_range, const 
     if (d->q_stride_head < d->head_dim || d->kv_stride_head < d->head_dim ||
         d->q_stride_tok < (int64_t)d->head_dim || d->kv_stride_tok < (int64_t)d->head_dim)
         return fail(HEXI_EINVAL, "strides must be at least head_dim");
+    // the bf16 kernels address the 64 rows of a tile through 32-bit byte offsets from the tile's first row
+    if (d->q_stride_tok > HEXI_MAX_TOKEN_STRIDE || d->kv_stride_tok > HEXI_MAX_TOKEN_STRIDE)
+        return fail(HEXI_EUNSUPPORTED, "token stride above %d elements", HEXI_MAX_TOKEN_STRIDE);
     const int esz = d->dtype == HEXI_BF16 ? 2 : 4;
     if ((d->q_stride_tok * esz) % 16 || (d->q_stride_head * esz) % 16 || (d->kv_stride_tok * esz) % 16 || (d->kv_stride_head * esz) % 16)
         return fail(HEXI_EALIGN, "token and head strides must be multiples of 16 bytes");

@@ -103,6 +103,8 @@ def test_descriptor_validation_returns_codes_without_launching():
     assert "flag" in hexi.hexi_last_error()
     bad = hexi.make_desc(hexi.HEXI_BF16, 96, 8, 2, 0.1, (768, 96), (192, 96))
     assert _call_fwd(bad, [(0, 4)], [(0, 4)], good) == hexi.HEXI_EUNSUPPORTED             # head_dim
+    bad = hexi.make_desc(hexi.HEXI_BF16, 128, 8, 2, 0.1, ((1 << 22) + 8, 128), (256, 128))
+    assert _call_fwd(bad, [(0, 4)], [(0, 4)], good) == hexi.HEXI_EUNSUPPORTED             # token stride beyond the 32-bit tile offsets
     bad = hexi.make_desc(7, 128, 8, 2, 0.1, (1024, 128), (256, 128))
     assert _call_fwd(bad, [(0, 4)], [(0, 4)], good) == hexi.HEXI_EUNSUPPORTED             # dtype
     bad = hexi.make_desc(hexi.HEXI_BF16, 128, 8, 3, 0.1, (1024, 128), (384, 128))
