@@ -64,7 +64,7 @@ struct HeadRuns {
 };
 
 template <int D, bool ATOMIC_DKV>
-__global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, const HeadRuns runs, const int n_kv_tiles)
+__global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, const HeadRuns runs, const int n_kv_tiles, const XcdSplit split)
 {
     static_assert(D == 64 || D == 128, "head_dim 64 or 128");
     constexpr int NKS = D / 16;     // 16-wide contraction steps across the head dimension
@@ -81,14 +81,13 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
     const int l32 = lane & 31, hh = lane >> 5;
     const int grp2 = (lane >> 4) & 1, j16 = lane & 15;
 
-    // Work mapping: consecutive workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a contiguous
-    // range of (head run, key tile) units so that the workgroups sharing an L2 stream the same heads' Q / dO tiles.
-    const int n_units = runs.n * n_kv_tiles;
+    // Work mapping: (head run, key tile) units, run-major; each XCD takes a contiguous unit range of about equal
+    // work, so that the workgroups sharing an L2 stream the same heads' Q / dO tiles.
     int unit;
     {
-        const int per = n_units / 8, rem = n_units % 8;
         const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-        unit = xcd * per + (xcd < rem ? xcd : rem) + slot;
+        unit = split.start[xcd] + slot;
+        if (unit >= split.start[xcd + 1]) return;
     }
     const int run = unit / n_kv_tiles;
     const int kv_tile = unit - run * n_kv_tiles;
@@ -438,7 +437,20 @@ hipError_t hexi_launch_bwd_bf16(const BwdArgs& a, hipStream_t s)
             }
             last[kh] = h;
         }
-        const unsigned grid = (unsigned)(runs.n * n_kv_tiles);
+        // cost of a unit: the q tiles its key tile sees, once per head of the run, plus the prologue and epilogue
+        // (about 20 tiles' worth)
+        float seen[4096];
+        const int n_known = n_kv_tiles < 4096 ? n_kv_tiles : 4096;     // (longer chunks: the remaining tiles count like the last known one)
+        for (int t = 0; t < n_known; ++t) {
+            const int k_min = seg_pos_of_row(a.g.ks, t * WG_KEYS);
+            const int n_all = n_qtiles - seg_rows_le(a.g.qs, k_min - 1) / TM;
+            seen[t] = (float)(n_all > 0 ? n_all : 0);
+        }
+        unsigned grid = 0;
+        const XcdSplit split = hexi_split_units(runs.n * n_kv_tiles, [&](int u) {
+            const int run = u / n_kv_tiles, t = u - run * n_kv_tiles;
+            return (float)runs.len[run] * seen[t < n_known ? t : n_known - 1] + 20.0f;
+        }, &grid);
         if ((shared || unused) && !a.accumulate) {
             const long long n = (long long)a.g.lc * a.g.nkv * a.g.d;
             hipError_t e = hexi_launch_fill_f32(a.dk, n, 0.f, s);
@@ -448,11 +460,11 @@ hipError_t hexi_launch_bwd_bf16(const BwdArgs& a, hipStream_t s)
         if (a.g.d != 128 && a.g.d != 64) return hipErrorInvalidValue;
         if (grid > 0) {
             if (a.g.d == 128) {
-                if (shared) bwd_dkdv_bf16_kernel<128, true><<<grid, 512, 0, s>>>(a, runs, n_kv_tiles);
-                else bwd_dkdv_bf16_kernel<128, false><<<grid, 512, 0, s>>>(a, runs, n_kv_tiles);
+                if (shared) bwd_dkdv_bf16_kernel<128, true><<<grid, 512, 0, s>>>(a, runs, n_kv_tiles, split);
+                else bwd_dkdv_bf16_kernel<128, false><<<grid, 512, 0, s>>>(a, runs, n_kv_tiles, split);
             } else {
-                if (shared) bwd_dkdv_bf16_kernel<64, true><<<grid, 512, 0, s>>>(a, runs, n_kv_tiles);
-                else bwd_dkdv_bf16_kernel<64, false><<<grid, 512, 0, s>>>(a, runs, n_kv_tiles);
+                if (shared) bwd_dkdv_bf16_kernel<64, true><<<grid, 512, 0, s>>>(a, runs, n_kv_tiles, split);
+                else bwd_dkdv_bf16_kernel<64, false><<<grid, 512, 0, s>>>(a, runs, n_kv_tiles, split);
             }
         }
         hipError_t e = hipGetLastError();

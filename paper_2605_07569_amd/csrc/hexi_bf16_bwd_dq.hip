@@ -37,7 +37,7 @@ template <int D> struct DqSmem {
 };
 
 template <int D>
-__global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const int n_q_tiles)
+__global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const int n_q_tiles, const XcdSplit split)
 {
     static_assert(D == 64 || D == 128, "head_dim 64 or 128");
     constexpr int NKS = D / 16;     // 16-wide contraction steps across the head dimension
@@ -56,13 +56,13 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
     const int l32 = lane & 31, hh = lane >> 5;
     const int grp2 = (lane >> 4) & 1, j16 = lane & 15;
 
-    // (head, q tile) units: contiguous ranges per XCD, longest q tiles of a head first
-    const int n_units = g.nq * n_q_tiles;
+    // (head, q tile) units, head-major, longest q tiles of a head first; each XCD takes a contiguous unit range of
+    // about equal work
     int unit;
     {
-        const int per = n_units / 8, rem = n_units % 8;
         const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-        unit = xcd * per + (xcd < rem ? xcd : rem) + slot;
+        unit = split.start[xcd] + slot;
+        if (unit >= split.start[xcd + 1]) return;
     }
     const int h = unit / n_q_tiles;
     const int q_tile = n_q_tiles - 1 - (unit - h * n_q_tiles);
@@ -349,10 +349,23 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
 
 hipError_t hexi_launch_bwd_dq_bf16(const BwdArgs& a, hipStream_t s)
 {
-    const int n_q_tiles = (a.g.lq + WG_ROWS - 1) / WG_ROWS;
-    const unsigned grid = (unsigned)(a.g.nq * n_q_tiles);
-    if (a.g.d == 128) bwd_dq_bf16_kernel<128><<<grid, 512, 0, s>>>(a, n_q_tiles);
-    else if (a.g.d == 64) bwd_dq_bf16_kernel<64><<<grid, 512, 0, s>>>(a, n_q_tiles);
+    const AttnGeom& g = a.g;
+    const int n_q_tiles = (g.lq + WG_ROWS - 1) / WG_ROWS;
+    // cost of a unit: the key tiles its q tile streams, plus the prologue and epilogue (about six tiles' worth); a
+    // unit that sees nothing of the chunk returns at once
+    float cost[4096];
+    const int n_known = n_q_tiles < 4096 ? n_q_tiles : 4096;     // (longer shards: the remaining tiles count like the last known one)
+    for (int p = 0; p < n_known; ++p) {
+        const int q_tile = n_q_tiles - 1 - p;
+        const int last_row = (q_tile * WG_ROWS + WG_ROWS < g.lq ? q_tile * WG_ROWS + WG_ROWS : g.lq) - 1;
+        const int nt = (seg_rows_le(g.ks, seg_pos_of_row(g.qs, last_row)) + TN - 1) / TN;
+        cost[p] = nt > 0 ? (float)nt + 6.0f : 0.25f;
+    }
+    unsigned grid = 0;
+    const XcdSplit split = hexi_split_units(g.nq * n_q_tiles, [&](int u) { const int p = u % n_q_tiles; return cost[p < n_known ? p : n_known - 1]; }, &grid);
+    if (grid == 0) return hipSuccess;
+    if (g.d == 128) bwd_dq_bf16_kernel<128><<<grid, 512, 0, s>>>(a, n_q_tiles, split);
+    else if (g.d == 64) bwd_dq_bf16_kernel<64><<<grid, 512, 0, s>>>(a, n_q_tiles, split);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

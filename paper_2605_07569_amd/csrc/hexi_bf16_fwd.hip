@@ -70,7 +70,7 @@ template <int D> struct FwdSmem {
 };
 
 template <int D>
-__global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const int n_q_tiles)
+__global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const int n_q_tiles, const XcdSplit split)
 {
     using C = FwdCfg<D>;
     constexpr int NKS = C::NKS, NDB = C::NDB, K_ROW_BYTES = C::K_ROW_BYTES, V_ROW_BYTES = C::V_ROW_BYTES;
@@ -86,16 +86,15 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
     const int l32 = lane & 31, hh = lane >> 5;
     const int grp2 = (lane >> 4) & 1, j16 = lane & 15;
 
-    // Work mapping: workgroup ids are dealt round-robin to the 8 XCDs; each XCD gets a contiguous
-    // range of (head, q tile) units, so the workgroups sharing an L2 stream the same kv head.  Within
-    // a head the q tiles are taken from the end of the shard backwards: under a causal mask the last
-    // tiles see the most keys, and starting the longest units first evens out the tail.
-    const int n_units = g.nq * n_q_tiles;
+    // Work mapping: (head, q tile) units, head-major; within a head the q tiles are taken from the end of the shard
+    // backwards (under a causal mask the last tiles see the most keys, and starting the longest units first evens
+    // out the tail).  Each XCD takes a contiguous unit range of about equal work, so the workgroups sharing an L2
+    // stream the same kv head.
     int unit;
     {
-        const int per = n_units / 8, rem = n_units % 8;
         const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-        unit = xcd * per + (xcd < rem ? xcd : rem) + slot;
+        unit = split.start[xcd] + slot;
+        if (unit >= split.start[xcd + 1]) return;
     }
     const int h = unit / n_q_tiles;
     const int q_tile = n_q_tiles - 1 - (unit - h * n_q_tiles);
@@ -463,10 +462,23 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
 
 hipError_t hexi_launch_fwd_bf16(const FwdArgs& a, hipStream_t s)
 {
-    const int n_q_tiles = (a.g.lq + WG_ROWS - 1) / WG_ROWS;
-    const unsigned grid = (unsigned)(a.g.nq * n_q_tiles);
-    if (a.g.d == 128) fwd_bf16_kernel<128><<<grid, 512, 0, s>>>(a, n_q_tiles);
-    else if (a.g.d == 64) fwd_bf16_kernel<64><<<grid, 512, 0, s>>>(a, n_q_tiles);
+    const AttnGeom& g = a.g;
+    const int n_q_tiles = (g.lq + WG_ROWS - 1) / WG_ROWS;
+    // cost of a unit: the key tiles its q tile streams, plus the prologue and epilogue (about six tiles' worth);
+    // a unit that sees nothing of the chunk returns at once under HEXI_ACCUMULATE and only writes zeros otherwise
+    float cost[4096];
+    const int n_known = n_q_tiles < 4096 ? n_q_tiles : 4096;     // (longer shards: the remaining tiles count like the last known one)
+    for (int p = 0; p < n_known; ++p) {
+        const int q_tile = n_q_tiles - 1 - p;
+        const int last_row = (q_tile * WG_ROWS + WG_ROWS < g.lq ? q_tile * WG_ROWS + WG_ROWS : g.lq) - 1;
+        const int nt = (seg_rows_le(g.ks, seg_pos_of_row(g.qs, last_row)) + TN - 1) / TN;
+        cost[p] = nt > 0 ? (float)nt + 6.0f : (a.accumulate ? 0.25f : 2.0f);
+    }
+    unsigned grid = 0;
+    const XcdSplit split = hexi_split_units(g.nq * n_q_tiles, [&](int u) { const int p = u % n_q_tiles; return cost[p < n_known ? p : n_known - 1]; }, &grid);
+    if (grid == 0) return hipSuccess;
+    if (g.d == 128) fwd_bf16_kernel<128><<<grid, 512, 0, s>>>(a, n_q_tiles, split);
+    else if (g.d == 64) fwd_bf16_kernel<64><<<grid, 512, 0, s>>>(a, n_q_tiles, split);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }

@@ -62,6 +62,37 @@ struct BwdArgs {
     int want_dq, want_dkdv;   // which halves of the backward step to run
 };
 
+// Work split over the 8 XCDs of the chip.  Workgroup ids are dealt round-robin to the XCDs (id % 8) and every XCD
+// starts its workgroups in id order, so workgroup `id` takes unit start[id % 8] + id / 8 of a launch whose units are
+// numbered so that neighbours share their streamed operands (same head, adjacent tiles): every XCD works on a
+// contiguous unit range, its L2 sees one head's stream at a time, and the ranges carry (nearly) equal WORK rather
+// than equal counts -- under a causal mask the units of a head differ in length by large factors, and equal counts
+// leave some XCDs idle for a sixth of a diagonal chunk's launch when a head's units straddle two XCDs.
+struct XcdSplit {
+    int start[9];     // XCD x takes units [start[x], start[x + 1])
+};
+
+// weight(u) > 0: estimated cost of unit u.  Returns the split and the grid size (8 x the longest range; workgroups
+// past the end of their XCD's range exit at once).
+template <class W> inline XcdSplit hexi_split_units(int n_units, W weight, unsigned* grid)
+{
+    double total = 0.0;
+    for (int u = 0; u < n_units; ++u) total += weight(u);
+    XcdSplit s;
+    s.start[0] = 0;
+    double acc = 0.0;
+    int x = 1;
+    for (int u = 0; u < n_units && x < 8; ++u) {
+        acc += weight(u);
+        while (x < 8 && acc * 8.0 >= total * x) s.start[x++] = u + 1;
+    }
+    while (x <= 8) s.start[x++] = n_units;
+    int longest = 0;
+    for (int i = 0; i < 8; ++i) longest = s.start[i + 1] - s.start[i] > longest ? s.start[i + 1] - s.start[i] : longest;
+    *grid = 8u * (unsigned)longest;
+    return s;
+}
+
 // Launchers (each returns a hipError_t from the launch).
 hipError_t hexi_launch_fwd_f32(const FwdArgs& a, hipStream_t s);
 hipError_t hexi_launch_bwd_f32(const BwdArgs& a, hipStream_t s);
