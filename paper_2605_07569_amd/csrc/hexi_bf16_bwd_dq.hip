@@ -9,9 +9,10 @@
 //   dQ^T += K^T dS^T  (K^T through transposed LDS reads; dS^T straight from the accumulator registers).
 //
 // Ping-pong schedule (see the forward kernel): two groups of four wavefronts, wavefront w and w + 4 on one
-// SIMD, alternate between a matrix phase and a vector phase with one workgroup barrier per phase, group 1 one
-// phase behind group 0, so that every SIMD always has one wavefront issuing only MFMAs (and their LDS reads)
-// and one issuing only VALU work.  A phase covers a 32-key block (half a 64-key LDS tile), which keeps the
+// SIMD, alternate between a matrix phase and a vector phase, group 1 one phase behind group 0, so that a SIMD
+// mostly has one wavefront issuing only MFMAs (and their LDS reads) and one issuing only VALU work.  One
+// workgroup barrier per pair of phases keeps the groups in step (group 0 passes it before a matrix phase,
+// group 1 before a vector phase).  A phase covers a 32-key block (half a 64-key LDS tile), which keeps the
 // scores and dP of one block only in registers:
 //   M(b): dQ^T += K^T dS^T of block b-1 (D / 16 MFMAs), then S^T and dP^T of block b (D / 8 MFMAs);
 //   V(b): P^T and dS^T of block b, dS^T rounded to bf16 operand slots.
@@ -251,20 +252,25 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
         asm volatile("" : "+v"(dsf[0]), "+v"(dsf[1]));
     };
 
-    // Phase sequence of a group: M(0) V(0) M(1) V(1) ... M(2 NT) over the 2 NT blocks, a barrier before every
-    // phase; group 1 starts one barrier late and group 0 ends with one extra.  Tile j must have landed before
+    // Phase sequence of a group: M(0) V(0) M(1) V(1) ... M(2 NT) over the 2 NT blocks; group 0 passes a workgroup
+    // barrier before every matrix phase, group 1 before its first matrix phase and before every vector phase
+    // (2 NT + 1 barriers each), which keeps group 1 one phase behind group 0.  Tile j must have landed before
     // group 0 enters M of its first block: group 0 (V) waits there, group 1 (K) waits before the vector phase
     // it runs in that same slot, V(2j - 1).  At that point tiles up to min(j + 2, NT - 1) have been requested.
     auto need_tile = [&](int j) __attribute__((always_inline)) {
         if (j < NT) wait_tiles_in_flight<DMA_PER_WAVE>((j + 2 < NT - 1 ? j + 2 : NT - 1) - j, my_xfers);
     };
     auto enter_m = [&](int blk) __attribute__((always_inline)) {
-        if (grp == 0 && (blk & 1) == 0) need_tile(blk >> 1);
-        wg_barrier();
+        if (grp == 0) {
+            if ((blk & 1) == 0) need_tile(blk >> 1);
+            wg_barrier();
+        }
     };
     auto vector_part = [&](int blk) __attribute__((always_inline)) {
-        if (grp == 1 && (blk & 1) == 1) need_tile((blk + 1) >> 1);
-        wg_barrier();
+        if (grp == 1) {
+            if ((blk & 1) == 1) need_tile((blk + 1) >> 1);
+            wg_barrier();
+        }
         const int t = blk >> 1;
         if ((blk & 1) == 0 && t + AHEAD < NT) fetch_tile(t + AHEAD);
         if (t >= n_full_g) v_phase(t & (2 * NB - 1), blk & 1, std::true_type{});
@@ -306,7 +312,6 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
         case 2: m_phase(IC<2>{}, IC<0>{}, IC<0>{}, IC<NDQ>{}); break;
         default: m_phase(IC<3>{}, IC<0>{}, IC<0>{}, IC<NDQ>{}); break;
     }
-    if (grp == 0) wg_barrier();
     __syncthreads();   // every wavefront is done with the tiles: LDS is free for the epilogue
 
     // Epilogue: dq_acc += scale * dQ.  The scaled rows go through LDS (a private 32 x (D + 4)-float region per

@@ -8,8 +8,10 @@
 // (wavefront w and w + 4 share a SIMD), each group owning 128 query rows, that alternate between
 //   M(t): the matrix phase  -- O^T += V^T P^T of tile t-1, then S^T = K Q^T of tile t (D / 4 MFMAs), and
 //   V(t): the vector phase  -- softmax numerators of tile t, P rounded to bf16 operand slots,
-// one workgroup barrier per phase, group 1 running one phase behind group 0, so that every SIMD always
-// has one wavefront in a matrix phase and one in a vector phase.  The vector-phase group also issues the
+// group 1 running one phase behind group 0, so that a SIMD mostly has one wavefront in a matrix phase and one
+// in a vector phase.  One workgroup barrier per tile keeps the groups in step and publishes the tiles that
+// have landed: group 0 passes it before its matrix phase, group 1 before its vector phase; the second phase
+// of each follows without a barrier (a barrier per phase was measured 2 % slower).  The vector-phase group also issues the
 // direct global->LDS loads of upcoming tiles (group 1 fetches K four tiles ahead, group 0 fetches V two
 // tiles ahead; four LDS buffers per tensor).
 //
@@ -312,8 +314,9 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
         asm volatile("" : "+v"(l_run), "+v"(lr_run), "+v"(pf[0]), "+v"(pf[1]), "+v"(pf[2]), "+v"(pf[3]));
     };
 
-    // One pass over the workgroup's tiles.  Phase sequence of a group: M(0) V(0) M(1) V(1) ... M(NT), a
-    // barrier before every phase; group 1 starts one barrier late and group 0 ends with one extra.  Both
+    // One pass over the workgroup's tiles.  Phase sequence of a group: M(0) V(0) M(1) V(1) ... M(NT); group 0
+    // passes a workgroup barrier before every matrix phase, group 1 before its first matrix phase and before
+    // every vector phase (NT + 1 barriers each), which keeps group 1 one phase behind group 0.  Both
     // groups walk all NT tiles (a group whose rows see fewer tiles masks the rest away), so the control
     // flow is the same everywhere.
     // (The softmax variant is a compile-time parameter: with a run-time flag the compiler keeps both variants'
@@ -336,16 +339,24 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
             wait_tiles_in_flight<DMA_PER_WAVE>((NT < K_AHEAD ? NT : K_AHEAD) - 1, my_xfers);
             wg_barrier();
         }
-        // before M(t): group 0 has requested V up to min(t + 1, NT - 1) and needs V(t - 1) complete
+        // One workgroup barrier B(t) per tile: group 0 passes it before M(t), group 1 before V(t - 1); between two
+        // barriers group 0 runs M(t) V(t) and group 1 runs V(t - 1) M(t) back to back, so the groups' matrix and
+        // vector phases still pair up but neither waits for the other in the middle.  Everything tile t's matrix
+        // phases read -- K(t), V(t - 1) -- has landed by B(t); the buffers refilled after B(t) were last read before it.
+        // before B(t): group 0 has requested V up to min(t + 1, NT - 1) and needs V(t - 1) complete
         auto enter_m = [&](int t) __attribute__((always_inline)) {
-            if (grp == 0) wait_tiles_in_flight<DMA_PER_WAVE>(NT - t < 2 ? NT - t : 2, my_xfers);
-            wg_barrier();
+            if (grp == 0) {
+                wait_tiles_in_flight<DMA_PER_WAVE>(NT - t < 2 ? NT - t : 2, my_xfers);
+                wg_barrier();
+            }
         };
-        // before V(t): group 1 has requested K up to min(t + 3, NT - 1) and needs K(t + 1) complete; then the
-        // vector phase itself, starting with this group's share of the fetches
+        // before V(t), i.e. B(t + 1): group 1 has requested K up to min(t + 3, NT - 1) and needs K(t + 1) complete;
+        // then the vector phase itself, starting with this group's share of the fetches
         auto vector_part = [&](int t, auto first_c) __attribute__((always_inline)) {
-            if (grp == 1 && t + 1 < NT) wait_tiles_in_flight<DMA_PER_WAVE>(NT - 2 - t < 2 ? NT - 2 - t : 2, my_xfers);
-            wg_barrier();
+            if (grp == 1) {
+                if (t + 1 < NT) wait_tiles_in_flight<DMA_PER_WAVE>(NT - 2 - t < 2 ? NT - 2 - t : 2, my_xfers);
+                wg_barrier();
+            }
             const int j = t + (grp ? K_AHEAD : V_AHEAD);
             if (j < NT) fetch_tile(j);
             if (t >= n_full_g) v_phase(t & (2 * NB - 1), first_c, std::true_type{}, exact);
@@ -380,7 +391,6 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
             case 2: m_phase(IC<2>{}, IC<0>{}, IC<NPV>{}); break;
             default: m_phase(IC<3>{}, IC<0>{}, IC<NPV>{}); break;
         }
-        if (grp == 0) wg_barrier();
     };
 
     run(std::false_type{});
