@@ -47,6 +47,9 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
     constexpr int N_XFER = P16_TILE_BYTES / 1024;          // wave-wide transfers per tile: 17 or 9
     constexpr int DMA_PER_WAVE = (N_XFER + 3) / 4;         // most transfers a wavefront issues per tile: 5 or 3
     constexpr int STAGE_STRIDE = D + 4;                    // floats per staged output row (epilogue)
+    // one workgroup barrier per pair of phases instead of one per phase (at head_dim 64, where the vector phase is by
+    // far the longer one, a barrier before every phase of both groups is faster; group 0 then ends with one extra)
+    constexpr bool PAIR_BARRIER = D == 128;
     static_assert(sizeof(DqSmem<D>) >= 8 * 32 * STAGE_STRIDE * 4, "epilogue staging does not fit");
     const AttnGeom& g = a.g;
     __shared__ __attribute__((aligned(1024))) DqSmem<D> sm;
@@ -261,16 +264,12 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
         if (j < NT) wait_tiles_in_flight<DMA_PER_WAVE>((j + 2 < NT - 1 ? j + 2 : NT - 1) - j, my_xfers);
     };
     auto enter_m = [&](int blk) __attribute__((always_inline)) {
-        if (grp == 0) {
-            if ((blk & 1) == 0) need_tile(blk >> 1);
-            wg_barrier();
-        }
+        if (grp == 0 && (blk & 1) == 0) need_tile(blk >> 1);
+        if (grp == 0 || !PAIR_BARRIER) wg_barrier();
     };
     auto vector_part = [&](int blk) __attribute__((always_inline)) {
-        if (grp == 1) {
-            if ((blk & 1) == 1) need_tile((blk + 1) >> 1);
-            wg_barrier();
-        }
+        if (grp == 1 && (blk & 1) == 1) need_tile((blk + 1) >> 1);
+        if (grp == 1 || !PAIR_BARRIER) wg_barrier();
         const int t = blk >> 1;
         if ((blk & 1) == 0 && t + AHEAD < NT) fetch_tile(t + AHEAD);
         if (t >= n_full_g) v_phase(t & (2 * NB - 1), blk & 1, std::true_type{});
@@ -312,6 +311,7 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
         case 2: m_phase(IC<2>{}, IC<0>{}, IC<0>{}, IC<NDQ>{}); break;
         default: m_phase(IC<3>{}, IC<0>{}, IC<0>{}, IC<NDQ>{}); break;
     }
+    if (!PAIR_BARRIER && grp == 0) wg_barrier();
     __syncthreads();   // every wavefront is done with the tiles: LDS is free for the epilogue
 
     // Epilogue: dq_acc += scale * dQ.  The scaled rows go through LDS (a private 32 x (D + 4)-float region per

@@ -78,6 +78,7 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
     constexpr int NKS = C::NKS, NDB = C::NDB, K_ROW_BYTES = C::K_ROW_BYTES, V_ROW_BYTES = C::V_ROW_BYTES;
     constexpr int K_TILE_BYTES = C::K_TILE_BYTES, V_TILE_BYTES = C::V_TILE_BYTES, DMA_PER_WAVE = C::DMA_PER_WAVE;
     constexpr int O_STAGE_STRIDE = C::O_STAGE_STRIDE;
+    constexpr bool PAIR_BARRIER = D == 128;     // one workgroup barrier per pair of phases instead of one per phase
     static_assert(sizeof(FwdSmem<D>) >= 8 * (32 * O_STAGE_STRIDE + 32) * 4, "epilogue staging does not fit");
     const AttnGeom& g = a.g;
     __shared__ __attribute__((aligned(1024))) FwdSmem<D> sm;
@@ -344,19 +345,17 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
         // vector phases still pair up but neither waits for the other in the middle.  Everything tile t's matrix
         // phases read -- K(t), V(t - 1) -- has landed by B(t); the buffers refilled after B(t) were last read before it.
         // before B(t): group 0 has requested V up to min(t + 1, NT - 1) and needs V(t - 1) complete
+        // (At head_dim 64, where the vector phase is by far the longer one, a barrier before every phase of both
+        // groups is faster: PAIR_BARRIER is off and group 0 ends with one extra barrier.)
         auto enter_m = [&](int t) __attribute__((always_inline)) {
-            if (grp == 0) {
-                wait_tiles_in_flight<DMA_PER_WAVE>(NT - t < 2 ? NT - t : 2, my_xfers);
-                wg_barrier();
-            }
+            if (grp == 0) wait_tiles_in_flight<DMA_PER_WAVE>(NT - t < 2 ? NT - t : 2, my_xfers);
+            if (grp == 0 || !PAIR_BARRIER) wg_barrier();
         };
         // before V(t), i.e. B(t + 1): group 1 has requested K up to min(t + 3, NT - 1) and needs K(t + 1) complete;
         // then the vector phase itself, starting with this group's share of the fetches
         auto vector_part = [&](int t, auto first_c) __attribute__((always_inline)) {
-            if (grp == 1) {
-                if (t + 1 < NT) wait_tiles_in_flight<DMA_PER_WAVE>(NT - 2 - t < 2 ? NT - 2 - t : 2, my_xfers);
-                wg_barrier();
-            }
+            if (grp == 1 && t + 1 < NT) wait_tiles_in_flight<DMA_PER_WAVE>(NT - 2 - t < 2 ? NT - 2 - t : 2, my_xfers);
+            if (grp == 1 || !PAIR_BARRIER) wg_barrier();
             const int j = t + (grp ? K_AHEAD : V_AHEAD);
             if (j < NT) fetch_tile(j);
             if (t >= n_full_g) v_phase(t & (2 * NB - 1), first_c, std::true_type{}, exact);
@@ -391,6 +390,7 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
             case 2: m_phase(IC<2>{}, IC<0>{}, IC<NPV>{}); break;
             default: m_phase(IC<3>{}, IC<0>{}, IC<NPV>{}); break;
         }
+        if (!PAIR_BARRIER && grp == 0) wg_barrier();
     };
 
     run(std::false_type{});
