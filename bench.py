@@ -4,10 +4,13 @@
 One step = one pass of the whole hot path over one synthetic shard: forward replay of the KV chunk
 list (fwd_chunk with the fused LSE merge), Delta, backward replay (bwd_chunk per chunk).  Inputs are
 resident in HBM before the timed region.  Prints one JSON line: fwd+bwd TFLOP/s counted on unmasked
-(query, key) pairs only (4*d forward + 10*d backward flops per pair per q head), the roofline
-position of the dominant kernel (the bf16 dK/dV backward kernel) measured with HIP events around its
-launches inside the timed region, and the fp64 CPU oracle timed on a bounded sample of the same
-workload as a reported baseline.
+(query, key) pairs only (4*d forward + 10*d backward flops per pair per q head) on the headline
+workload -- configuration 4, the largest single-GPU shard (8B-like, 512K tokens, 16 chunks) -- the
+roofline position of the dominant kernel (the bf16 dK/dV backward kernel) measured with HIP events
+around its launches inside the timed region, the other bf16 configurations (2, 3, 5) timed the same
+way over fewer steps under "other_workloads", the zigzag configurations replayed with contiguous
+chunks under "contiguous_chunk_replay", and the fp64 CPU oracle timed on a bounded sample of the
+headline workload as a reported baseline.  Progress lines go to stderr.
 """
 import argparse
 import json
@@ -19,7 +22,7 @@ import torch
 PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16 MFMA peak: 256 CU x 2.4 GHz x 4096 flop/clk/CU
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # command (see profiles/); None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {"cfg2_3b_zigzag": 0.676e9}   # bwd_dkdv_bf16_kernel<false>: 496 MB fetched + 180 MB written
+MEASURED_TRAFFIC_BYTES = {"cfg2_3b_zigzag": 0.676e9}   # bwd_dkdv_bf16_kernel<128,false>: 496 MB fetched + 180 MB written
 
 
 def parse():
@@ -27,9 +30,14 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", type=int, default=2, help="shard configuration 1..5 (default 2: the 3B-like zigzag shard)")
+    ap.add_argument("--workload", type=int, default=4,
+                    help="headline shard configuration 1..5 (default 4: the 8B-like 512K zigzag shard, the largest one)")
     ap.add_argument("--head-dim", type=int, default=0,
                     help="variant run: the same shard with this head_dim (64 or 128) instead of the configuration's own")
+    ap.add_argument("--only-headline", action="store_true",
+                    help="time the headline workload only (no other configurations, no contiguous-chunk replay, no "
+                         "HBM-bound kernels, no MFMA probe, no oracle): the command the rocprofv3 summaries are made with")
+    ap.add_argument("--no-others", action="store_true", help="skip the other bf16 configurations and the contiguous-chunk replays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a kernel of known HBM traffic) before the timed "
@@ -39,23 +47,14 @@ def parse():
     return ap.parse_args()
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py measures one GPU's share of the ring on one MI355X; --gpus above 1 is not supported "
-              "(no collectives are part of this build)", file=sys.stderr)
-        sys.exit(2)
-    from paper_2605_07569_amd import hexi, replay
-    from paper_2605_07569_amd import workloads as wl
+def log(msg):
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
 
-    hexi.load()   # raises if the HIP library is not built: no fallback path exists
-    torch.cuda.set_device(0)
-    w = wl.config(args.workload)
-    if args.head_dim and args.head_dim != w.head_dim:
-        import dataclasses
-        w = dataclasses.replace(w, head_dim=args.head_dim, name=f"{w.name}_d{args.head_dim}",
-                                note=w.note + f" (variant: head_dim {args.head_dim})")
-    inputs = wl.make_inputs(w)
+
+def measure(w, inputs, steps, warmup, copy_calibration=False):
+    """Times `steps` passes of the whole hot path (forward replay, Delta, backward replay) over workload `w` after
+    `warmup` untimed ones.  Returns (result dict, ShardRun)."""
+    from paper_2605_07569_amd import hexi, replay
     run = replay.ShardRun(w, inputs, "cuda:0", fused_merge=True)
     n_pairs_chunk = [hexi.hexi_shard_mask(w.q_segs, ch, want_pos=False)["n_pairs"] for ch in w.chunks]
     n_pairs = sum(n_pairs_chunk)
@@ -63,11 +62,16 @@ def main():
     flops_fwd = 4.0 * d * n_pairs * nq
     flops_bwd = 10.0 * d * n_pairs * nq
     live = [j for j, n in enumerate(n_pairs_chunk) if n > 0]       # chunks that launch the attention kernels
+    # the dominant kernel's launches that are timed one by one: the chunks other than the diagonal one(s), i.e.
+    # those in which no key lies inside a q segment (all of their tiles are unmasked or invisible)
+    def has_diagonal(ch):
+        return any(ks < qs + qn and qs < ks + kn for qs, qn in w.q_segs for ks, kn in ch)
+    remote = [j for j in live if not has_diagonal(w.chunks[j])]
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         run.step()
     torch.cuda.synchronize()
-    if args.copy_calibration:
+    if copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").fill_(1.0)   # 1 GiB read + 1 GiB written
         dst = torch.empty_like(src)
         dst.copy_(src)
@@ -76,8 +80,9 @@ def main():
 
     ev = lambda: torch.cuda.Event(enable_timing=True)
     fwd_ev, bwd_ev, kern_ev = [], [], []
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         e0, e1, e2 = ev(), ev(), ev()
         e0.record()
         run.forward()
@@ -95,7 +100,7 @@ def main():
             kb.record()
             hexi.hexi_attn_bwd_chunk(run.desc[j], w.q_segs, ch, run.q, run.k[j], run.v[j], run.o, run.d_o,
                                      run.lse, run.delta, run.dq, None, None, flags=hexi.HEXI_SKIP_DKDV)
-            if j in live and j != 0:
+            if j in remote and j != 0:
                 kern_ev.append((j, ka, kb))
         e2.record()
         fwd_ev.append((e0, e1))
@@ -103,9 +108,9 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
 
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    fwd_ms = sum(a.elapsed_time(b) for a, b in fwd_ev) / args.steps
-    bwd_ms = sum(a.elapsed_time(b) for a, b in bwd_ev) / args.steps
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    fwd_ms = sum(a.elapsed_time(b) for a, b in fwd_ev) / steps
+    bwd_ms = sum(a.elapsed_time(b) for a, b in bwd_ev) / steps
     step_ms = sorted(f[0].elapsed_time(b[1]) for f, b in zip(fwd_ev, bwd_ev))     # per-step device time
     tflops = (flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12
 
@@ -116,7 +121,7 @@ def main():
     if kern_ev:
         k_ms = sum(a.elapsed_time(b) for _, a, b in kern_ev) / len(kern_ev)
         k_flops = sum(8.0 * d * nq * n_pairs_chunk[j] for j, _, _ in kern_ev) / len(kern_ev)
-    else:  # single live chunk: fall back to the whole backward replay
+    else:  # no remote chunk besides the first: fall back to the whole backward replay
         k_ms, k_flops = bwd_ms, flops_bwd
     achieved = k_flops / (k_ms * 1e-3) / 1e12
     is_bf16 = w.dtype == "bf16"
@@ -124,12 +129,9 @@ def main():
     roofline = {"bound": "mfma" if is_bf16 else "alu", "kernel": "bwd_dkdv_bf16_kernel" if is_bf16 else "bwd_f32_kernel",
                 "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                 "traffic": MEASURED_TRAFFIC_BYTES.get(w.name), "launch_ms": round(k_ms, 4),
-                "flops_per_launch": k_flops}
-
-    out = {"metric": "attention fwd+bwd TFLOP/s per shard on 1 MI355X; % of bf16 MFMA peak",
-           "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-           "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-           "dtype": w.dtype, "data": "synthetic",
+                "flops_per_launch": k_flops, "launches_timed": len(kern_ev) // max(1, steps)}
+    res = {"value": round(tflops, 2), "unit": "TFLOP/s", "steps": steps, "warmup": warmup,
+           "ms_per_step": round(ms_per_step, 4), "dtype": w.dtype,
            "config": {"workload": w.name, "note": w.note, "n_q_heads": nq, "n_kv_heads": w.n_kv_heads, "head_dim": d,
                       "q_rows": w.lq, "kv_chunks": len(w.chunks), "unmasked_pairs_per_head": n_pairs,
                       "counted_tflop_per_step": round((flops_fwd + flops_bwd) / 1e12, 3)},
@@ -139,20 +141,81 @@ def main():
            "fwd_tflops": round(flops_fwd / (fwd_ms * 1e-3) / 1e12, 2),
            "bwd_tflops": round(flops_bwd / (bwd_ms * 1e-3) / 1e12, 2),
            "roofline": roofline}
-
     # The paper's own cost convention (App. A.4, Eq. 11): 16 * L_q * L_src * n_d * d_h per ring step, no causal
     # discount, recomputation counted as a separate pass; summed here over the steps that see at least one key.
     paper_flops = sum(16.0 * w.lq * sum(n for _, n in w.chunks[j]) * nq * d for j in live)
-    out["paper_convention"] = {"tflop_per_step": round(paper_flops / 1e12, 3),
+    res["paper_convention"] = {"tflop_per_step": round(paper_flops / 1e12, 3),
                                "tflops": round(paper_flops / (ms_per_step * 1e-3) / 1e12, 2),
                                "note": "16*Lq*Lc*nq*d per live ring step (App. A.4 Eq. 11), masked pairs included"}
-    out["hbm_bound_kernels"] = hbm_bound_kernels(run, w)
-    if is_bf16 and not args.no_mfma_probe:
+    return res, run, n_pairs
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU's share of the ring on one MI355X; --gpus above 1 is not supported "
+              "(no collectives are part of this build)", file=sys.stderr)
+        sys.exit(2)
+    from paper_2605_07569_amd import hexi
+    from paper_2605_07569_amd import workloads as wl
+
+    hexi.load()   # raises if the HIP library is not built: no fallback path exists
+    torch.cuda.set_device(0)
+    w = wl.config(args.workload)
+    if args.head_dim and args.head_dim != w.head_dim:
+        import dataclasses
+        w = dataclasses.replace(w, head_dim=args.head_dim, name=f"{w.name}_d{args.head_dim}",
+                                note=w.note + f" (variant: head_dim {args.head_dim})")
+    log(f"generating inputs of {w.name} on the host")
+    inputs = wl.make_inputs(w)
+    log(f"timing {w.name}: {args.warmup} warm-up + {args.steps} steps")
+    res, run, n_pairs = measure(w, inputs, args.steps, args.warmup, args.copy_calibration)
+    out = {"metric": "attention fwd+bwd TFLOP/s per shard on 1 MI355X; % of bf16 MFMA peak",
+           "value": res["value"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": w.dtype, "data": "synthetic"}
+    out.update({k: v for k, v in res.items() if k not in out})
+    is_bf16 = w.dtype == "bf16"
+    if not args.only_headline:
+        out["hbm_bound_kernels"] = hbm_bound_kernels(run, w)
+    del run
+    torch.cuda.empty_cache()
+    if is_bf16 and not args.no_mfma_probe and not args.only_headline:
         out["mfma_probe"] = mfma_probe()
         # context only: frac stays against the nominal peak
-        out["roofline"]["frac_of_measured_mfma_rate"] = round(achieved / out["mfma_probe"]["random_tflops"], 4)
+        out["roofline"]["frac_of_measured_mfma_rate"] = round(out["roofline"]["achieved"] / out["mfma_probe"]["random_tflops"], 4)
 
-    if not args.no_cpu_baseline:
+    if not args.only_headline and not args.no_others and not args.head_dim:
+        # the zigzag configurations with the alternative reading of "chunk": the same keys as equal contiguous
+        # chunks (parity of this chunking is a test; its time stands beside the zigzag-pair replay's)
+        contig = {}
+        others = {}
+        short_steps, short_warm = max(1, min(args.steps, 5)), 2
+        for idx in (2, 3, 4, 5):
+            wi = wl.config(idx)
+            if idx == args.workload:
+                inp = inputs
+            else:
+                log(f"generating inputs of {wi.name}")
+                inp = wl.make_inputs(wi)
+                log(f"timing {wi.name}: {short_warm} warm-up + {short_steps} steps")
+                r, run_i, _ = measure(wi, inp, short_steps, short_warm)
+                del run_i
+                torch.cuda.empty_cache()
+                others[wi.name] = r
+            if len(wi.q_segs) == 2:     # a zigzag shard
+                wc = wl.contiguous_chunks(wi, len(wi.chunks))
+                log(f"timing {wc.name}")
+                r, run_i, _ = measure(wc, inp, short_steps, short_warm)
+                del run_i
+                torch.cuda.empty_cache()
+                contig[wc.name] = {k: r[k] for k in ("value", "unit", "ms_per_step", "fwd_tflops", "bwd_tflops", "steps", "warmup")}
+            del inp
+        out["other_workloads"] = others
+        out["contiguous_chunk_replay"] = contig
+
+    if not args.no_cpu_baseline and not args.only_headline:
+        log("timing the fp64 oracle on a sample of the headline workload (host cores)")
         out["cpu_baseline"] = cpu_baseline(w, inputs, args.cpu_rows, n_pairs)
     print(json.dumps(out), flush=True)
 

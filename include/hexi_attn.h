@@ -137,8 +137,8 @@ int hexi_attn_merge_lse(int64_t n_rows, int32_t n_q_heads, int32_t head_dim,
  * heads that share a kv head are summed inside one workgroup when the launch is large enough
  * without splitting them (dk/dv are then reproducible run to run); otherwise groups are cut into
  * runs of heads whose contributions are summed with floating-point atomics, whose order (and so
- * the last bits of dk/dv) can vary between runs.  The environment variable HEXI_DKDV_RUN_LEN
- * (>= 1) overrides the run length chosen by the library.  HEXI_SKIP_DQ / HEXI_SKIP_DKDV
+ * the last bits of dk/dv) can vary between runs.  hexi_set_dkdv_run_len() overrides the run length
+ * chosen by the library.  HEXI_SKIP_DQ / HEXI_SKIP_DKDV
  * restrict the call to one of the two halves (they are separate kernels and may be issued on
  * different streams); both set is HEXI_EINVAL.  A chunk
  * wholly in the shard's future writes zeros to dk/dv (nothing under HEXI_ACCUMULATE) and leaves
@@ -240,13 +240,14 @@ int hexi_sched_solve(const hexi_cluster* cluster, const hexi_model* model, const
                      hexi_schedule* out, double* cost);
 
 /*
- * Measurement aid: a register-only loop of v_mfma_f32_32x32x16_bf16 on the whole chip (256 workgroups
- * x 8 wavefronts x 4 x iters MFMAs of 32768 flop), for the MFMA rate the part sustains on given
- * operand bits (the shader clock is power-limited and depends on them).  operands: DEVICE, 65536
- * bytes of bf16 values, 16-byte aligned; sink: DEVICE float[256 * 512], overwritten.  Enqueued on
- * hip_stream; the caller times it.
+ * Tuning / test knob of hexi_attn_bwd_chunk's dK/dV part (the GQA sum over the n_d local heads of a
+ * group, Sec. 3.2): the number of q heads of one kv head that a workgroup walks into the same
+ * accumulators.  0 = chosen by the library per call (the default); n >= 1 = at most n (clamped to
+ * the largest group).  The initial value is read once, when the library is loaded, from the
+ * environment variable HEXI_DKDV_RUN_LEN.  Process-wide; not synchronised with calls in flight on
+ * other threads.  Returns the previous value.
  */
-int hexi_mfma_probe(const void* operands, float* sink, int32_t iters, void* hip_stream);
+int32_t hexi_set_dkdv_run_len(int32_t run_len);
 
 /* Bytes of device workspace the chunk calls need for this descriptor and these lengths
  * (currently 0: no kernel uses scratch memory). */

@@ -8,6 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhexi_attn.so")
+PROBE_LIB = os.path.join(HERE, "libhexi_probe.so")      # the benchmark's measurement aid (include/hexi_probe.h)
+EXPORT_MAP = os.path.join(CSRC, "hexi_exports.map")     # only hexi_* symbols leave the libraries
 SOURCES = ["hexi_api.hip", "hexi_sched.cpp", "hexi_misc.hip", "hexi_a2a.hip", "hexi_f32.hip", "hexi_bf16_fwd.hip", "hexi_bf16_bwd.hip", "hexi_bf16_bwd_dq.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-munsafe-fp-atomics", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -38,12 +40,13 @@ def _compile(src):
 
 
 def build(verbose=True):
-    with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
-        objs = list(ex.map(_compile, SOURCES))
-    cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-pthread", "-o", LIB] + objs
-    subprocess.check_call(cmd)
+    with ThreadPoolExecutor(max_workers=len(SOURCES) + 1) as ex:
+        objs = list(ex.map(_compile, SOURCES + ["hexi_probe.hip"]))
+    link = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-pthread", "-Wl,--version-script=" + EXPORT_MAP]
+    subprocess.check_call(link + ["-o", LIB] + objs[:-1])
+    subprocess.check_call(link + ["-o", PROBE_LIB] + objs[-1:])
     if verbose:
-        print("built", LIB)
+        print("built", LIB, "and", PROBE_LIB)
     return LIB
 
 

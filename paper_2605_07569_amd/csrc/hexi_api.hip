@@ -1,6 +1,7 @@
 // Host side of the C ABI: argument validation, segment tables, integer mask bookkeeping, dispatch.
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <cmath>
 #include <vector>
@@ -9,6 +10,15 @@
 #define HEXI_EXPORT extern "C" __attribute__((visibility("default")))
 
 static thread_local char g_err[320] = "";
+
+// forced run length of the dK/dV launcher (0: automatic); initial value from the environment, read once
+static int env_run_len()
+{
+    const char* v = getenv("HEXI_DKDV_RUN_LEN");
+    const int n = v ? atoi(v) : 0;
+    return n > 0 ? n : 0;
+}
+int hexi_dkdv_run_len = env_run_len();
 
 static int fail(int code, const char* fmt, ...)
 {
@@ -150,6 +160,13 @@ static bool chunk_in_future(const AttnGeom& g)
     return g.ks.start[0] > q_max;
 }
 
+HEXI_EXPORT int32_t hexi_set_dkdv_run_len(int32_t run_len)
+{
+    const int32_t old = hexi_dkdv_run_len;
+    hexi_dkdv_run_len = run_len > 0 ? run_len : 0;
+    return old;
+}
+
 HEXI_EXPORT size_t hexi_workspace_bytes(const hexi_attn_desc*, int64_t, int64_t) { return 0; }
 
 HEXI_EXPORT int hexi_attn_fwd_chunk(const hexi_attn_desc* desc, const hexi_range* q_range, const hexi_range* kv_range,
@@ -211,7 +228,7 @@ HEXI_EXPORT int hexi_attn_bwd_chunk(const hexi_attn_desc* desc, const hexi_range
         return fail(HEXI_EINVAL, "null tensor pointer");
     if ((flags & HEXI_COMPUTE_DELTA) && !o) return fail(HEXI_EINVAL, "HEXI_COMPUTE_DELTA needs o");
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || (want_dq && !aligned16(dq_acc)) ||
-        (want_dkdv && (!aligned16(dk) || !aligned16(dv))) ||
+        (want_dkdv && (!aligned16(dk) || !aligned16(dv))) || !aligned16(lse) || !aligned16(delta) ||
         ((flags & HEXI_COMPUTE_DELTA) && !aligned16(o)))
         return fail(HEXI_EALIGN, "tensor base pointers must be 16-byte aligned");
     hipStream_t s = (hipStream_t)hip_stream;
@@ -286,13 +303,3 @@ HEXI_EXPORT int hexi_a2a_unpack(const void* packed, void* y, int64_t s, int32_t 
 {
     return a2a_call(false, nullptr, const_cast<void*>(packed), y, s, n_heads_total, head_dim, elem_bytes, y_stride_tok, n_ranks, heads_per_rank, head_list, hip_stream);
 }
-
-HEXI_EXPORT int hexi_mfma_probe(const void* operands, float* sink, int32_t iters, void* hip_stream)
-{
-    if (!operands || !sink || iters < 1) return fail(HEXI_EINVAL, "null pointer or iters < 1");
-    if (!aligned16(operands)) return fail(HEXI_EALIGN, "operands must be 16-byte aligned");
-    hipError_t e = hexi_launch_mfma_probe(operands, sink, iters, (hipStream_t)hip_stream);
-    if (e != hipSuccess) return fail(HEXI_EHIP, "probe launch failed: %s", hipGetErrorString(e));
-    return HEXI_OK;
-}
-

@@ -29,7 +29,6 @@
 // run).  When a kv head has a single run its tiles are written with plain stores; otherwise the runs add theirs
 // with fp32 atomics, and dk/dv must be zero-filled (or hold the running sum under HEXI_ACCUMULATE) before the
 // launch.  The host picks the run length: as long as possible while the launch still has a few workgroups per CU.
-#include <cstdlib>
 #include "hexi_internal.h"
 #include "hexi_mfma.h"
 
@@ -55,13 +54,6 @@ __host__ __device__ constexpr int reads_of(int st, int ndb)
 {
     return st < 4 * ndb ? 2 + ((st == 2 * ndb || st == 3 * ndb) ? 1 : 0) : 1;
 }
-
-// Runs of q heads: run r covers len[r] heads starting at first[r], linked through next[] (all read kv head
-// kv_of_q[first[r]]).
-struct HeadRuns {
-    int n;
-    signed char first[HEXI_MAX_HEADS], len[HEXI_MAX_HEADS], next[HEXI_MAX_HEADS];
-};
 
 template <int D, bool ATOMIC_DKV>
 __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, const HeadRuns runs, const int n_kv_tiles, const XcdSplit split)
@@ -413,30 +405,10 @@ hipError_t hexi_launch_bwd_bf16(const BwdArgs& a, hipStream_t s)
         while (run_len > 1 && (max_cnt % run_len != 0 || (long long)run_len * max_tiles > 512 ||
                                (long long)n_runs_for(run_len) * n_kv_tiles < 3 * 256))
             --run_len;
-        if (const char* forced = getenv("HEXI_DKDV_RUN_LEN")) {     // tuning / test override of the heuristic
-            const int v = atoi(forced);
-            if (v >= 1) run_len = v < max_cnt ? v : max_cnt;
-        }
+        if (const int forced = hexi_dkdv_run_len; forced >= 1)      // tuning / test override of the heuristic
+            run_len = forced < max_cnt ? forced : max_cnt;
         HeadRuns runs;
-        runs.n = 0;
-        int last[HEXI_MAX_HEADS], open_run[HEXI_MAX_HEADS];   // per kv head: its last q head so far, its run being filled
-        bool shared = false;
-        for (int kh = 0; kh < a.g.nkv; ++kh) { last[kh] = -1; open_run[kh] = -1; }
-        for (int h = 0; h < a.g.nq; ++h) {
-            const int kh = a.g.kv_of_q[h];
-            runs.next[h] = -1;
-            if (open_run[kh] >= 0 && runs.len[open_run[kh]] < run_len) {
-                runs.next[last[kh]] = (signed char)h;
-                ++runs.len[open_run[kh]];
-            } else {
-                shared |= open_run[kh] >= 0;     // a second run on this kv head: the runs add their tiles atomically
-                open_run[kh] = runs.n;
-                runs.first[runs.n] = (signed char)h;
-                runs.len[runs.n] = 1;
-                ++runs.n;
-            }
-            last[kh] = h;
-        }
+        const bool shared = hexi_build_head_runs(a.g.kv_of_q, a.g.nq, a.g.nkv, run_len, &runs);
         // cost of a unit: the q tiles its key tile sees, once per head of the run, plus the prologue and epilogue
         // (about 20 tiles' worth)
         float seen[4096];

@@ -17,7 +17,7 @@
 //
 // As before the scores are computed transposed (S^T = K Q^T) so that every lane owns one query row,
 // softmax state is a per-lane scalar, and the accumulator registers holding P^T are already in MFMA
-// operand order for O^T += V^T P^T.  K / V tiles (64 keys) are XOR-swizzled in LDS so that the 128-bit
+// operand order for O^T += V^T P^T.  K / V tiles (64 keys) sit in LDS with padded rows so that the 128-bit
 // row reads of K and the transposed 64-bit reads of V are bank-conflict free.
 //
 // Softmax reference.  The vector phase must stay short (it is the co-limiter), so the fast path does not
@@ -62,13 +62,12 @@ constexpr float RESCALE_SLACK = 8.0f;
 constexpr float SUM_LO = 8.6736174e-19f;   // 2^-60
 constexpr float SUM_HI = 1.1529215e18f;    // 2^60
 
-__device__ __forceinline__ int swz_row(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
-
 template <int D> struct FwdSmem {
     unsigned char k[NB][FwdCfg<D>::K_TILE_BYTES];   // 4 x 17 KB (D = 128)
     unsigned char v[NB][FwdCfg<D>::V_TILE_BYTES];   // 4 x 20 KB
     int kpos[2 * NB][TN];     // key positions of the tiles that need a mask, written K_AHEAD tiles ahead
-    // the epilogue stages 8 x (32 x (D + 4) + 32) floats over the start of this struct
+    // The epilogue stages 8 x (32 x (D + 4) + 32) floats over the start of this struct: the regions of wavefronts
+    // 4..7 lie over v[], so every wavefront must be done with the tiles (a workgroup barrier) before any stages.
 };
 
 template <int D>
@@ -403,6 +402,9 @@ __global__ void __launch_bounds__(512) fwd_bf16_kernel(const FwdArgs a, const in
             run(std::true_type{});
             l_tot = sum_across_halves(l_run);
             lr_tot = sum_across_halves(lr_run);
+            // the last matrix phase of the other wavefronts may still be reading V tiles that the staging below
+            // overwrites (after the fast pass the vote above is that barrier)
+            __syncthreads();
         }
     }
 

@@ -93,6 +93,43 @@ template <class W> inline XcdSplit hexi_split_units(int n_units, W weight, unsig
     return s;
 }
 
+// Runs of q heads for the dK/dV kernel: run r covers len[r] heads starting at first[r], linked through next[] (all
+// read kv head kv_of_q[first[r]]).
+struct HeadRuns {
+    int n;
+    signed char first[HEXI_MAX_HEADS], next[HEXI_MAX_HEADS];
+    unsigned char len[HEXI_MAX_HEADS];     // up to HEXI_MAX_HEADS = 128 heads in one run
+};
+
+// Cuts the q heads of every kv head, in head order, into runs of at most run_len heads.  Returns true when some kv
+// head has more than one run (its runs then add their dK / dV tiles with atomics).
+inline bool hexi_build_head_runs(const signed char* kv_of_q, int nq, int nkv, int run_len, HeadRuns* runs)
+{
+    int last[HEXI_MAX_HEADS], open_run[HEXI_MAX_HEADS];   // per kv head: its last q head so far, its run being filled
+    bool shared = false;
+    runs->n = 0;
+    for (int kh = 0; kh < nkv; ++kh) { last[kh] = -1; open_run[kh] = -1; }
+    for (int h = 0; h < nq; ++h) {
+        const int kh = kv_of_q[h];
+        runs->next[h] = -1;
+        if (open_run[kh] >= 0 && runs->len[open_run[kh]] < run_len) {
+            runs->next[last[kh]] = (signed char)h;
+            ++runs->len[open_run[kh]];
+        } else {
+            shared |= open_run[kh] >= 0;     // a second run on this kv head
+            open_run[kh] = runs->n;
+            runs->first[runs->n] = (signed char)h;
+            runs->len[runs->n] = 1;
+            ++runs->n;
+        }
+        last[kh] = h;
+    }
+    return shared;
+}
+
+// Forced number of q heads per dK/dV workgroup run (0: the launcher chooses); see hexi_set_dkdv_run_len().
+extern int hexi_dkdv_run_len;
+
 // Launchers (each returns a hipError_t from the launch).
 hipError_t hexi_launch_fwd_f32(const FwdArgs& a, hipStream_t s);
 hipError_t hexi_launch_bwd_f32(const BwdArgs& a, hipStream_t s);
@@ -104,7 +141,6 @@ hipError_t hexi_launch_merge(long long n_rows, int nq, int d, float* o_acc, floa
 hipError_t hexi_launch_delta(long long lq, int nq, int d, const float* o, const void* d_o, int dtype,
                              long long stride_tok, long long stride_head, float* delta, hipStream_t s);
 hipError_t hexi_launch_fill_f32(float* p, long long n, float value, hipStream_t s);
-hipError_t hexi_launch_mfma_probe(const void* operands, float* sink, int iters, hipStream_t s);
 // pack (x -> packed) or unpack (packed -> y, which has x's layout); host tables, validated by the caller
 hipError_t hexi_launch_a2a(bool pack, const void* x, void* packed, void* y, long long s, int n_heads_total, int row_bytes,
                            long long x_stride_bytes, int n_ranks, const int* heads_per_rank, const int* head_list, hipStream_t st);

@@ -2,6 +2,8 @@
 #include "hexi_internal.h"
 #include <hip/hip_bf16.h>
 
+namespace {
+
 // One thread per 4 consecutive head_dim elements of one (row, head); this pass only reads the lse
 // arrays (merge_lse_kernel rewrites lse_acc afterwards, so no thread ever sees a replaced value).
 // o_*: [n_rows][nq][d] fp32, lse_*: [nq][n_rows].  Weights are formed as e_a/(e_a+e_b) with
@@ -53,6 +55,8 @@ __global__ void __launch_bounds__(256) merge_lse_kernel(long long n, float* __re
     lse_acc[i] = (m == -INFINITY) ? -INFINITY : m + logf(expf(a - m) + expf(b - m));
 }
 
+}  // namespace
+
 hipError_t hexi_launch_merge(long long n_rows, int nq, int d, float* o_acc, float* lse_acc, const float* o_part,
                              const float* lse_part, void* o_final, int o_final_dtype, hipStream_t s)
 {
@@ -71,6 +75,8 @@ hipError_t hexi_launch_merge(long long n_rows, int nq, int d, float* o_acc, floa
     merge_lse_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(n, lse_acc, lse_part);
     return hipGetLastError();
 }
+
+namespace {
 
 // Delta[h][i] = sum_c dO[i][h][c] * O[i][h][c]; O fp32 dense, dO in the input dtype with strides.
 // D/4 consecutive lanes share one (row, head).
@@ -106,6 +112,8 @@ __global__ void __launch_bounds__(256) delta_kernel(long long lq, int nq, const 
     if (valid && c4 == 0) delta[(long long)h * lq + row] = acc;
 }
 
+}  // namespace
+
 hipError_t hexi_launch_delta(long long lq, int nq, int d, const float* o, const void* d_o, int dtype,
                              long long stride_tok, long long stride_head, float* delta, hipStream_t s)
 {
@@ -121,12 +129,16 @@ hipError_t hexi_launch_delta(long long lq, int nq, int d, const float* o, const 
     return hipGetLastError();
 }
 
+namespace {
+
 __global__ void __launch_bounds__(256) fill_kernel(float* __restrict__ p, long long n, float value)
 {
     long long i = (long long)blockIdx.x * 256 + threadIdx.x;
     const long long stride = (long long)gridDim.x * 256;
     for (; i < n; i += stride) p[i] = value;
 }
+
+}  // namespace
 
 hipError_t hexi_launch_fill_f32(float* p, long long n, float value, hipStream_t s)
 {
@@ -136,30 +148,3 @@ hipError_t hexi_launch_fill_f32(float* p, long long n, float value, hipStream_t 
     fill_kernel<<<(unsigned)blocks, 256, 0, s>>>(p, n, value);
     return hipGetLastError();
 }
-
-// Register-only MFMA loop: what the matrix cores sustain on given operand bits with nothing else going on.
-// 256 workgroups x 8 wavefronts (two per SIMD), four independent accumulators per wavefront.
-typedef float probe_f32x16 __attribute__((ext_vector_type(16)));
-typedef __bf16 probe_bf16x8 __attribute__((ext_vector_type(8)));
-__global__ void __launch_bounds__(512) mfma_probe_kernel(const probe_bf16x8* __restrict__ in, float* __restrict__ sink, int iters)
-{
-    probe_bf16x8 a[4], b[4];
-    for (int i = 0; i < 4; ++i) { a[i] = in[(threadIdx.x * 8 + i) % 4096]; b[i] = in[(threadIdx.x * 8 + 4 + i) % 4096]; }
-    probe_f32x16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
-    for (int i = 0; i < iters; ++i) {
-        c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[0], c0, 0, 0, 0);
-        c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1], b[1], c1, 0, 0, 0);
-        c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2], b[2], c2, 0, 0, 0);
-        c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[3], b[3], c3, 0, 0, 0);
-    }
-    float s = 0.f;
-    for (int r = 0; r < 16; ++r) s += c0[r] + c1[r] + c2[r] + c3[r];
-    sink[blockIdx.x * 512 + threadIdx.x] = s;
-}
-
-hipError_t hexi_launch_mfma_probe(const void* operands, float* sink, int iters, hipStream_t s)
-{
-    mfma_probe_kernel<<<256, 512, 0, s>>>(static_cast<const probe_bf16x8*>(operands), sink, iters);
-    return hipGetLastError();
-}
-

@@ -19,11 +19,14 @@ HEXI_TILE_EMPTY, HEXI_TILE_FULL, HEXI_TILE_PARTIAL = 0, 1, 2
 HEXI_MAX_SEGS = 16
 
 EXPORTS = ("hexi_shard_mask", "hexi_attn_fwd_chunk", "hexi_attn_merge_lse", "hexi_attn_bwd_chunk",
-           "hexi_a2a_pack", "hexi_a2a_unpack", "hexi_sched_cost", "hexi_sched_solve", "hexi_mfma_probe", "hexi_workspace_bytes", "hexi_last_error", "hexi_version")
+           "hexi_a2a_pack", "hexi_a2a_unpack", "hexi_sched_cost", "hexi_sched_solve", "hexi_set_dkdv_run_len", "hexi_workspace_bytes", "hexi_last_error", "hexi_version")
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libhexi_attn.so")
+PROBE_LIB_PATH = os.path.join(_HERE, "libhexi_probe.so")     # include/hexi_probe.h: the benchmark's MFMA rate probe
+PROBE_EXPORTS = ("hexi_mfma_probe",)
 _lib = None
+_probe_lib = None
 
 
 class HexiError(RuntimeError):
@@ -77,14 +80,28 @@ def load():
     lib.hexi_sched_cost.restype = ctypes.c_int
     lib.hexi_sched_solve.argtypes = [vp, vp, vp, vp, ctypes.POINTER(ctypes.c_double)]
     lib.hexi_sched_solve.restype = ctypes.c_int
-    lib.hexi_mfma_probe.argtypes = [vp, vp, i32, vp]
-    lib.hexi_mfma_probe.restype = ctypes.c_int
+    lib.hexi_set_dkdv_run_len.argtypes = [i32]
+    lib.hexi_set_dkdv_run_len.restype = i32
     lib.hexi_workspace_bytes.argtypes = [dp, i64, i64]
     lib.hexi_workspace_bytes.restype = ctypes.c_size_t
     lib.hexi_last_error.restype = ctypes.c_char_p
     lib.hexi_version.restype = ctypes.c_char_p
     _lib = lib
     return lib
+
+
+def load_probe():
+    """Loads the benchmark's measurement-aid library (not part of the attention interface)."""
+    global _probe_lib
+    if _probe_lib is None:
+        if not os.path.exists(PROBE_LIB_PATH):
+            raise RuntimeError(f"{PROBE_LIB_PATH} is missing: build it with `python -m paper_2605_07569_amd.build`")
+        import torch  # noqa: F401
+        lib = ctypes.CDLL(PROBE_LIB_PATH)
+        lib.hexi_mfma_probe.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p]
+        lib.hexi_mfma_probe.restype = ctypes.c_int
+        _probe_lib = lib
+    return _probe_lib
 
 
 def _check(rc):
@@ -285,7 +302,14 @@ def hexi_sched_solve(cluster, model, **opts):
                 cost=cost.value)
 
 
+def hexi_set_dkdv_run_len(run_len):
+    """0: the library chooses per call; n >= 1: at most n q heads per dK/dV workgroup run.  Returns the previous value."""
+    return int(load().hexi_set_dkdv_run_len(int(run_len)))
+
+
 def hexi_mfma_probe(operands, sink, iters, stream=None):
     """operands: 65536 bytes of bf16 on the device; sink: float32[256 * 512] on the device."""
-    _check(load().hexi_mfma_probe(_ptr(operands), _ptr(sink), int(iters), _stream(stream)))
+    rc = load_probe().hexi_mfma_probe(_ptr(operands), _ptr(sink), int(iters), _stream(stream))
+    if rc != 0:
+        raise HexiError(rc, "hexi_mfma_probe refused its arguments or the launch")
 

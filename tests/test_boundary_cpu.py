@@ -4,6 +4,7 @@ validation returns the documented error codes before anything is launched."""
 import ctypes
 import os
 import re
+import subprocess
 
 import numpy as np
 import pytest
@@ -15,16 +16,39 @@ from paper_2605_07569_amd import workloads as wl
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "hexi_attn.h")).read()
+def _declared(header_name):
+    header = open(os.path.join(ROOT, "include", header_name)).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(hexi_[a-z0-9_]+)\s*\(", header))
+    return set(re.findall(r"\b(hexi_[a-z0-9_]+)\s*\(", header))
+
+
+def _dynamic_symbols(path):
+    out = subprocess.run(["nm", "-D", "--defined-only", path], capture_output=True, text=True, check=True).stdout
+    return {line.split()[-1] for line in out.splitlines() if line.strip()}
+
+
+def test_library_exports_every_declared_symbol():
+    """Every function a header under include/ declares is exported by that header's library, the binding knows
+    the same names, and nothing else leaves the libraries (no kernel stubs, no C++ library symbols)."""
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["hexi_attn.h", "hexi_probe.h"]
+    declared = _declared("hexi_attn.h")
     assert {"hexi_shard_mask", "hexi_attn_fwd_chunk", "hexi_attn_merge_lse", "hexi_attn_bwd_chunk"} <= declared
     lib = hexi.load()
     for name in declared:
         assert hasattr(lib, name), name
     assert declared == set(hexi.EXPORTS)
+    assert _dynamic_symbols(hexi.LIB_PATH) == declared
     assert "gfx950" in hexi.hexi_version()
+    probe = hexi.load_probe()
+    declared = _declared("hexi_probe.h")
+    assert declared == set(hexi.PROBE_EXPORTS) and all(hasattr(probe, n) for n in declared)
+    assert _dynamic_symbols(hexi.PROBE_LIB_PATH) == declared
+
+
+def test_run_length_knob_round_trip():
+    assert hexi.hexi_set_dkdv_run_len(3) == 0
+    assert hexi.hexi_set_dkdv_run_len(-5) == 3      # negative values mean automatic
+    assert hexi.hexi_set_dkdv_run_len(0) == 0
 
 
 def _random_segs(rng, n_seg, max_len, max_gap):

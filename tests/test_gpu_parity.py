@@ -18,6 +18,13 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
+@pytest.fixture
+def force_run_len():
+    """Sets the dK/dV launcher's forced head-run length for the test and restores the automatic choice after it."""
+    yield hexi.hexi_set_dkdv_run_len
+    hexi.hexi_set_dkdv_run_len(0)
+
+
 def _run_and_compare(w, seed=20260507, fused=True, grad_abs_factor=1.0):
     """Runs the whole replay on the GPU and compares every element of every output with the oracle.
     `grad_abs_factor` widens only the max-abs bound of dq/dk (see test_tier1_minis_full_tensor)."""
@@ -113,12 +120,12 @@ def test_explicit_head_map_and_single_rows():
 
 
 @pytest.mark.parametrize("run_len", [1, 2, 3, 8])
-def test_dkdv_head_runs(run_len, monkeypatch):
+def test_dkdv_head_runs(run_len, force_run_len):
     # The dK/dV kernel walks runs of q heads that share a kv head in one workgroup; the launcher picks the
     # run length from the launch size, so small shapes would only ever see runs of one head.  Force the
     # length: whole groups (no atomics), runs with a remainder (3 of 5), non-adjacent heads of a group,
     # groups of unequal size, masked + full + ragged tiles in every head of a run.
-    monkeypatch.setenv("HEXI_DKDV_RUN_LEN", str(run_len))
+    force_run_len(run_len)
     w = _custom(f"runs{run_len}", "bf16", 8, 3, 128, 700, [(150, 70), (400, 300)], [[(0, 333)], [(333, 367)]],
                 kv_of_q=[0, 1, 0, 0, 2, 0, 1, 0])
     _run_and_compare(w, seed=21)
@@ -167,7 +174,7 @@ def test_randomized_longer_shards():
         _run_and_compare(w, seed=200 + i, fused=bool(i % 2))
 
 
-def test_bf16_head_dim_64_minis_and_head_runs(monkeypatch):
+def test_bf16_head_dim_64_minis_and_head_runs(force_run_len):
     # the bf16 kernels at head_dim 64 (the smaller models' heads): configurations 2 and 5 shrunk, heads halved to
     # 64 columns (zigzag pairs, one GQA group of 8, FULL + diagonal + EMPTY chunks), fused and unfused
     import dataclasses
@@ -176,7 +183,7 @@ def test_bf16_head_dim_64_minis_and_head_runs(monkeypatch):
         _run_and_compare(w, fused=(idx == 2))
     # forced dK/dV head runs: whole groups, runs with a remainder, non-adjacent heads of a group
     for run_len in (1, 3, 8):
-        monkeypatch.setenv("HEXI_DKDV_RUN_LEN", str(run_len))
+        force_run_len(run_len)
         w = _custom(f"runs{run_len}_d64", "bf16", 8, 3, 64, 700, [(150, 70), (400, 300)], [[(0, 333)], [(333, 367)]],
                     kv_of_q=[0, 1, 0, 0, 2, 0, 1, 0])
         _run_and_compare(w, seed=31)
@@ -198,11 +205,10 @@ def test_bf16_head_dim_64_workgroup_boundary_sizes(lq, lc):
 
 
 @pytest.mark.parametrize("run_len", [0, 1, 2])
-def test_strided_inputs_and_accumulate_flags(run_len, monkeypatch):
+def test_strided_inputs_and_accumulate_flags(run_len, force_run_len):
     # (also with forced dK/dV head runs: whole groups in one workgroup add to the running dk/dv without
     # atomics, split groups with them)
-    if run_len:
-        monkeypatch.setenv("HEXI_DKDV_RUN_LEN", str(run_len))
+    force_run_len(run_len)
     # q/dO and k/v are slices of wider buffers (token and head strides larger than dense)
     w = _custom("strided", "bf16", 4, 2, 128, 512, [(128, 384)], [[(0, 256)], [(256, 256)]])
     inputs = wl.make_inputs(w, 5)
