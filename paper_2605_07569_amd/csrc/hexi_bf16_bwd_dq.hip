@@ -30,6 +30,304 @@ constexpr int WG_ROWS = 256;       // q rows per workgroup
 constexpr int AHEAD = 3;           // tile j + 3 is requested during tile j
 constexpr float LOG2E = 1.4426950408889634f;
 
+// A 32-key block in which some |dS| reaches this value also accumulates the residuals dS - bf16(dS) of the rounding:
+// rounding dS to bf16 costs up to 2^-9 |dS| scale |k| per element of dQ, which for the few keys that dominate a
+// sharply peaked row (|dS| of several units) is most of the output tolerance.
+constexpr float DS_SPLIT = 2.0f;
+
+// dQ^T += K^T (dS^T - bf16(dS^T)) for one 32-key block, executed only when `any_large` (a wave-uniform lane mask) is
+// non-zero: a few blocks in a thousand even on sharply peaked rows, so the path is written for simplicity, with fp32
+// MFMAs (v_mfma_f32_32x32x2_f32: every operand is one register per lane; accumulator register x of a lane pairs its
+// two half-waves' keys).  ds[0..15]: the lane's dS^T values in fp32; hw[0..7]: their bf16 roundings, two per dword;
+// ka: the lane's LDS byte address of K[first key of the block + (lane / 32)][2 * (lane % 32)] in the tile's padded,
+// row-permuted image (row pitch ROW): accumulator register x = 4b + t holds key 8b + 4 (lane / 32) + t, stored in
+// LDS row 16 (b / 2) + 4 t + 2 (b % 2) + (lane / 32) of the block.  The branch lives inside the assembly statement so
+// that the compiler sees straight-line code (a visible branch around MFMAs makes it copy the accumulators at the merge).
+template <int NDB, int ROW>
+__device__ __forceinline__ void dq_add_residuals(f32x16 (&dq)[NDB], const float (&ds)[16], const uint32_t (&hw)[8], uint32_t ka,
+                                                 unsigned long long any_large)
+{
+    static_assert(NDB == 4 || NDB == 2, "two or four 32-column blocks");
+    float t_k, t_r;
+    if constexpr (NDB == 4) {
+        asm volatile(
+            "s_cmp_eq_u64 %[f], 0\n\ts_cbranch_scc1 .Lhexi_skip%=\n\ts_nop 15\n\ts_nop 15\n\t"
+            "v_lshlrev_b32 %[r], 16, %[h0]\n\t"
+            "v_sub_f32 %[r], %[d0], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o0_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o0_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o0_2]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a2], %[t], %[r], %[a2]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o0_3]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a3], %[t], %[r], %[a3]\n\t"
+            "v_and_b32 %[r], 0xffff0000, %[h0]\n\t"
+            "v_sub_f32 %[r], %[d1], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o1_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o1_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o1_2]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a2], %[t], %[r], %[a2]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o1_3]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a3], %[t], %[r], %[a3]\n\t"
+            "v_lshlrev_b32 %[r], 16, %[h1]\n\t"
+            "v_sub_f32 %[r], %[d2], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o2_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o2_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o2_2]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a2], %[t], %[r], %[a2]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o2_3]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a3], %[t], %[r], %[a3]\n\t"
+            "v_and_b32 %[r], 0xffff0000, %[h1]\n\t"
+            "v_sub_f32 %[r], %[d3], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o3_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o3_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o3_2]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a2], %[t], %[r], %[a2]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o3_3]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a3], %[t], %[r], %[a3]\n\t"
+            "v_lshlrev_b32 %[r], 16, %[h2]\n\t"
+            "v_sub_f32 %[r], %[d4], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o4_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o4_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o4_2]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a2], %[t], %[r], %[a2]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o4_3]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a3], %[t], %[r], %[a3]\n\t"
+            "v_and_b32 %[r], 0xffff0000, %[h2]\n\t"
+            "v_sub_f32 %[r], %[d5], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o5_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o5_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o5_2]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a2], %[t], %[r], %[a2]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o5_3]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a3], %[t], %[r], %[a3]\n\t"
+            "v_lshlrev_b32 %[r], 16, %[h3]\n\t"
+            "v_sub_f32 %[r], %[d6], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o6_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o6_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o6_2]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a2], %[t], %[r], %[a2]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o6_3]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a3], %[t], %[r], %[a3]\n\t"
+            "v_and_b32 %[r], 0xffff0000, %[h3]\n\t"
+            "v_sub_f32 %[r], %[d7], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o7_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o7_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o7_2]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a2], %[t], %[r], %[a2]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o7_3]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a3], %[t], %[r], %[a3]\n\t"
+            "v_lshlrev_b32 %[r], 16, %[h4]\n\t"
+            "v_sub_f32 %[r], %[d8], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o8_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o8_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o8_2]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a2], %[t], %[r], %[a2]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o8_3]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a3], %[t], %[r], %[a3]\n\t"
+            "v_and_b32 %[r], 0xffff0000, %[h4]\n\t"
+            "v_sub_f32 %[r], %[d9], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o9_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o9_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o9_2]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a2], %[t], %[r], %[a2]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o9_3]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a3], %[t], %[r], %[a3]\n\t"
+            "v_lshlrev_b32 %[r], 16, %[h5]\n\t"
+            "v_sub_f32 %[r], %[d10], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o10_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o10_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o10_2]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a2], %[t], %[r], %[a2]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o10_3]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a3], %[t], %[r], %[a3]\n\t"
+            "v_and_b32 %[r], 0xffff0000, %[h5]\n\t"
+            "v_sub_f32 %[r], %[d11], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o11_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o11_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o11_2]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a2], %[t], %[r], %[a2]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o11_3]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a3], %[t], %[r], %[a3]\n\t"
+            "v_lshlrev_b32 %[r], 16, %[h6]\n\t"
+            "v_sub_f32 %[r], %[d12], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o12_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o12_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o12_2]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a2], %[t], %[r], %[a2]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o12_3]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a3], %[t], %[r], %[a3]\n\t"
+            "v_and_b32 %[r], 0xffff0000, %[h6]\n\t"
+            "v_sub_f32 %[r], %[d13], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o13_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o13_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o13_2]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a2], %[t], %[r], %[a2]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o13_3]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a3], %[t], %[r], %[a3]\n\t"
+            "v_lshlrev_b32 %[r], 16, %[h7]\n\t"
+            "v_sub_f32 %[r], %[d14], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o14_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o14_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o14_2]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a2], %[t], %[r], %[a2]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o14_3]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a3], %[t], %[r], %[a3]\n\t"
+            "v_and_b32 %[r], 0xffff0000, %[h7]\n\t"
+            "v_sub_f32 %[r], %[d15], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o15_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o15_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o15_2]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a2], %[t], %[r], %[a2]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o15_3]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a3], %[t], %[r], %[a3]\n\t"
+            "s_nop 15\n\ts_nop 15\n\t"
+            ".Lhexi_skip%=:"
+            : [a0] "+v"(dq[0]), [a1] "+v"(dq[1]), [a2] "+v"(dq[2]), [a3] "+v"(dq[3]), [t] "=&v"(t_k), [r] "=&v"(t_r)
+            : [f] "s"(any_large), [ka] "v"(ka), [h0] "v"(hw[0]), [h1] "v"(hw[1]), [h2] "v"(hw[2]), [h3] "v"(hw[3]), [h4] "v"(hw[4]), [h5] "v"(hw[5]), [h6] "v"(hw[6]), [h7] "v"(hw[7]),
+              [d0] "v"(ds[0]), [d1] "v"(ds[1]), [d2] "v"(ds[2]), [d3] "v"(ds[3]), [d4] "v"(ds[4]), [d5] "v"(ds[5]), [d6] "v"(ds[6]), [d7] "v"(ds[7]), [d8] "v"(ds[8]), [d9] "v"(ds[9]), [d10] "v"(ds[10]), [d11] "v"(ds[11]), [d12] "v"(ds[12]), [d13] "v"(ds[13]), [d14] "v"(ds[14]), [d15] "v"(ds[15]),
+              [o0_0] "n"((16 * (0 >> 1) + 4 * 0 + 2 * (0 & 1)) * ROW + 64 * 0), [o0_1] "n"((16 * (0 >> 1) + 4 * 0 + 2 * (0 & 1)) * ROW + 64 * 1), [o0_2] "n"((16 * (0 >> 1) + 4 * 0 + 2 * (0 & 1)) * ROW + 64 * 2), [o0_3] "n"((16 * (0 >> 1) + 4 * 0 + 2 * (0 & 1)) * ROW + 64 * 3), [o1_0] "n"((16 * (0 >> 1) + 4 * 1 + 2 * (0 & 1)) * ROW + 64 * 0), [o1_1] "n"((16 * (0 >> 1) + 4 * 1 + 2 * (0 & 1)) * ROW + 64 * 1), [o1_2] "n"((16 * (0 >> 1) + 4 * 1 + 2 * (0 & 1)) * ROW + 64 * 2), [o1_3] "n"((16 * (0 >> 1) + 4 * 1 + 2 * (0 & 1)) * ROW + 64 * 3), [o2_0] "n"((16 * (0 >> 1) + 4 * 2 + 2 * (0 & 1)) * ROW + 64 * 0), [o2_1] "n"((16 * (0 >> 1) + 4 * 2 + 2 * (0 & 1)) * ROW + 64 * 1), [o2_2] "n"((16 * (0 >> 1) + 4 * 2 + 2 * (0 & 1)) * ROW + 64 * 2), [o2_3] "n"((16 * (0 >> 1) + 4 * 2 + 2 * (0 & 1)) * ROW + 64 * 3), [o3_0] "n"((16 * (0 >> 1) + 4 * 3 + 2 * (0 & 1)) * ROW + 64 * 0), [o3_1] "n"((16 * (0 >> 1) + 4 * 3 + 2 * (0 & 1)) * ROW + 64 * 1), [o3_2] "n"((16 * (0 >> 1) + 4 * 3 + 2 * (0 & 1)) * ROW + 64 * 2), [o3_3] "n"((16 * (0 >> 1) + 4 * 3 + 2 * (0 & 1)) * ROW + 64 * 3), [o4_0] "n"((16 * (1 >> 1) + 4 * 0 + 2 * (1 & 1)) * ROW + 64 * 0), [o4_1] "n"((16 * (1 >> 1) + 4 * 0 + 2 * (1 & 1)) * ROW + 64 * 1), [o4_2] "n"((16 * (1 >> 1) + 4 * 0 + 2 * (1 & 1)) * ROW + 64 * 2), [o4_3] "n"((16 * (1 >> 1) + 4 * 0 + 2 * (1 & 1)) * ROW + 64 * 3), [o5_0] "n"((16 * (1 >> 1) + 4 * 1 + 2 * (1 & 1)) * ROW + 64 * 0), [o5_1] "n"((16 * (1 >> 1) + 4 * 1 + 2 * (1 & 1)) * ROW + 64 * 1), [o5_2] "n"((16 * (1 >> 1) + 4 * 1 + 2 * (1 & 1)) * ROW + 64 * 2), [o5_3] "n"((16 * (1 >> 1) + 4 * 1 + 2 * (1 & 1)) * ROW + 64 * 3), [o6_0] "n"((16 * (1 >> 1) + 4 * 2 + 2 * (1 & 1)) * ROW + 64 * 0), [o6_1] "n"((16 * (1 >> 1) + 4 * 2 + 2 * (1 & 1)) * ROW + 64 * 1), [o6_2] "n"((16 * (1 >> 1) + 4 * 2 + 2 * (1 & 1)) * ROW + 64 * 2), [o6_3] "n"((16 * (1 >> 1) + 4 * 2 + 2 * (1 & 1)) * ROW + 64 * 3), [o7_0] "n"((16 * (1 >> 1) + 4 * 3 + 2 * (1 & 1)) * ROW + 64 * 0), [o7_1] "n"((16 * (1 >> 1) + 4 * 3 + 2 * (1 & 1)) * ROW + 64 * 1), [o7_2] "n"((16 * (1 >> 1) + 4 * 3 + 2 * (1 & 1)) * ROW + 64 * 2), [o7_3] "n"((16 * (1 >> 1) + 4 * 3 + 2 * (1 & 1)) * ROW + 64 * 3), [o8_0] "n"((16 * (2 >> 1) + 4 * 0 + 2 * (2 & 1)) * ROW + 64 * 0), [o8_1] "n"((16 * (2 >> 1) + 4 * 0 + 2 * (2 & 1)) * ROW + 64 * 1), [o8_2] "n"((16 * (2 >> 1) + 4 * 0 + 2 * (2 & 1)) * ROW + 64 * 2), [o8_3] "n"((16 * (2 >> 1) + 4 * 0 + 2 * (2 & 1)) * ROW + 64 * 3), [o9_0] "n"((16 * (2 >> 1) + 4 * 1 + 2 * (2 & 1)) * ROW + 64 * 0), [o9_1] "n"((16 * (2 >> 1) + 4 * 1 + 2 * (2 & 1)) * ROW + 64 * 1), [o9_2] "n"((16 * (2 >> 1) + 4 * 1 + 2 * (2 & 1)) * ROW + 64 * 2), [o9_3] "n"((16 * (2 >> 1) + 4 * 1 + 2 * (2 & 1)) * ROW + 64 * 3), [o10_0] "n"((16 * (2 >> 1) + 4 * 2 + 2 * (2 & 1)) * ROW + 64 * 0), [o10_1] "n"((16 * (2 >> 1) + 4 * 2 + 2 * (2 & 1)) * ROW + 64 * 1), [o10_2] "n"((16 * (2 >> 1) + 4 * 2 + 2 * (2 & 1)) * ROW + 64 * 2), [o10_3] "n"((16 * (2 >> 1) + 4 * 2 + 2 * (2 & 1)) * ROW + 64 * 3), [o11_0] "n"((16 * (2 >> 1) + 4 * 3 + 2 * (2 & 1)) * ROW + 64 * 0), [o11_1] "n"((16 * (2 >> 1) + 4 * 3 + 2 * (2 & 1)) * ROW + 64 * 1), [o11_2] "n"((16 * (2 >> 1) + 4 * 3 + 2 * (2 & 1)) * ROW + 64 * 2), [o11_3] "n"((16 * (2 >> 1) + 4 * 3 + 2 * (2 & 1)) * ROW + 64 * 3), [o12_0] "n"((16 * (3 >> 1) + 4 * 0 + 2 * (3 & 1)) * ROW + 64 * 0), [o12_1] "n"((16 * (3 >> 1) + 4 * 0 + 2 * (3 & 1)) * ROW + 64 * 1), [o12_2] "n"((16 * (3 >> 1) + 4 * 0 + 2 * (3 & 1)) * ROW + 64 * 2), [o12_3] "n"((16 * (3 >> 1) + 4 * 0 + 2 * (3 & 1)) * ROW + 64 * 3), [o13_0] "n"((16 * (3 >> 1) + 4 * 1 + 2 * (3 & 1)) * ROW + 64 * 0), [o13_1] "n"((16 * (3 >> 1) + 4 * 1 + 2 * (3 & 1)) * ROW + 64 * 1), [o13_2] "n"((16 * (3 >> 1) + 4 * 1 + 2 * (3 & 1)) * ROW + 64 * 2), [o13_3] "n"((16 * (3 >> 1) + 4 * 1 + 2 * (3 & 1)) * ROW + 64 * 3), [o14_0] "n"((16 * (3 >> 1) + 4 * 2 + 2 * (3 & 1)) * ROW + 64 * 0), [o14_1] "n"((16 * (3 >> 1) + 4 * 2 + 2 * (3 & 1)) * ROW + 64 * 1), [o14_2] "n"((16 * (3 >> 1) + 4 * 2 + 2 * (3 & 1)) * ROW + 64 * 2), [o14_3] "n"((16 * (3 >> 1) + 4 * 2 + 2 * (3 & 1)) * ROW + 64 * 3), [o15_0] "n"((16 * (3 >> 1) + 4 * 3 + 2 * (3 & 1)) * ROW + 64 * 0), [o15_1] "n"((16 * (3 >> 1) + 4 * 3 + 2 * (3 & 1)) * ROW + 64 * 1), [o15_2] "n"((16 * (3 >> 1) + 4 * 3 + 2 * (3 & 1)) * ROW + 64 * 2), [o15_3] "n"((16 * (3 >> 1) + 4 * 3 + 2 * (3 & 1)) * ROW + 64 * 3)
+            : "scc", "memory");
+    } else {
+        asm volatile(
+            "s_cmp_eq_u64 %[f], 0\n\ts_cbranch_scc1 .Lhexi_skip%=\n\ts_nop 15\n\ts_nop 15\n\t"
+            "v_lshlrev_b32 %[r], 16, %[h0]\n\t"
+            "v_sub_f32 %[r], %[d0], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o0_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o0_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "v_and_b32 %[r], 0xffff0000, %[h0]\n\t"
+            "v_sub_f32 %[r], %[d1], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o1_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o1_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "v_lshlrev_b32 %[r], 16, %[h1]\n\t"
+            "v_sub_f32 %[r], %[d2], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o2_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o2_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "v_and_b32 %[r], 0xffff0000, %[h1]\n\t"
+            "v_sub_f32 %[r], %[d3], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o3_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o3_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "v_lshlrev_b32 %[r], 16, %[h2]\n\t"
+            "v_sub_f32 %[r], %[d4], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o4_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o4_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "v_and_b32 %[r], 0xffff0000, %[h2]\n\t"
+            "v_sub_f32 %[r], %[d5], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o5_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o5_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "v_lshlrev_b32 %[r], 16, %[h3]\n\t"
+            "v_sub_f32 %[r], %[d6], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o6_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o6_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "v_and_b32 %[r], 0xffff0000, %[h3]\n\t"
+            "v_sub_f32 %[r], %[d7], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o7_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o7_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "v_lshlrev_b32 %[r], 16, %[h4]\n\t"
+            "v_sub_f32 %[r], %[d8], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o8_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o8_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "v_and_b32 %[r], 0xffff0000, %[h4]\n\t"
+            "v_sub_f32 %[r], %[d9], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o9_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o9_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "v_lshlrev_b32 %[r], 16, %[h5]\n\t"
+            "v_sub_f32 %[r], %[d10], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o10_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o10_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "v_and_b32 %[r], 0xffff0000, %[h5]\n\t"
+            "v_sub_f32 %[r], %[d11], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o11_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o11_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "v_lshlrev_b32 %[r], 16, %[h6]\n\t"
+            "v_sub_f32 %[r], %[d12], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o12_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o12_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "v_and_b32 %[r], 0xffff0000, %[h6]\n\t"
+            "v_sub_f32 %[r], %[d13], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o13_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o13_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "v_lshlrev_b32 %[r], 16, %[h7]\n\t"
+            "v_sub_f32 %[r], %[d14], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o14_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o14_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "v_and_b32 %[r], 0xffff0000, %[h7]\n\t"
+            "v_sub_f32 %[r], %[d15], %[r]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o15_0]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a0], %[t], %[r], %[a0]\n\t"
+            "ds_read_u16 %[t], %[ka] offset:%c[o15_1]\n\ts_waitcnt lgkmcnt(0)\n\tv_lshlrev_b32 %[t], 16, %[t]\n\ts_nop 1\n\t"
+            "v_mfma_f32_32x32x2_f32 %[a1], %[t], %[r], %[a1]\n\t"
+            "s_nop 15\n\ts_nop 15\n\t"
+            ".Lhexi_skip%=:"
+            : [a0] "+v"(dq[0]), [a1] "+v"(dq[1]), [t] "=&v"(t_k), [r] "=&v"(t_r)
+            : [f] "s"(any_large), [ka] "v"(ka), [h0] "v"(hw[0]), [h1] "v"(hw[1]), [h2] "v"(hw[2]), [h3] "v"(hw[3]), [h4] "v"(hw[4]), [h5] "v"(hw[5]), [h6] "v"(hw[6]), [h7] "v"(hw[7]),
+              [d0] "v"(ds[0]), [d1] "v"(ds[1]), [d2] "v"(ds[2]), [d3] "v"(ds[3]), [d4] "v"(ds[4]), [d5] "v"(ds[5]), [d6] "v"(ds[6]), [d7] "v"(ds[7]), [d8] "v"(ds[8]), [d9] "v"(ds[9]), [d10] "v"(ds[10]), [d11] "v"(ds[11]), [d12] "v"(ds[12]), [d13] "v"(ds[13]), [d14] "v"(ds[14]), [d15] "v"(ds[15]),
+              [o0_0] "n"((16 * (0 >> 1) + 4 * 0 + 2 * (0 & 1)) * ROW + 64 * 0), [o0_1] "n"((16 * (0 >> 1) + 4 * 0 + 2 * (0 & 1)) * ROW + 64 * 1), [o1_0] "n"((16 * (0 >> 1) + 4 * 1 + 2 * (0 & 1)) * ROW + 64 * 0), [o1_1] "n"((16 * (0 >> 1) + 4 * 1 + 2 * (0 & 1)) * ROW + 64 * 1), [o2_0] "n"((16 * (0 >> 1) + 4 * 2 + 2 * (0 & 1)) * ROW + 64 * 0), [o2_1] "n"((16 * (0 >> 1) + 4 * 2 + 2 * (0 & 1)) * ROW + 64 * 1), [o3_0] "n"((16 * (0 >> 1) + 4 * 3 + 2 * (0 & 1)) * ROW + 64 * 0), [o3_1] "n"((16 * (0 >> 1) + 4 * 3 + 2 * (0 & 1)) * ROW + 64 * 1), [o4_0] "n"((16 * (1 >> 1) + 4 * 0 + 2 * (1 & 1)) * ROW + 64 * 0), [o4_1] "n"((16 * (1 >> 1) + 4 * 0 + 2 * (1 & 1)) * ROW + 64 * 1), [o5_0] "n"((16 * (1 >> 1) + 4 * 1 + 2 * (1 & 1)) * ROW + 64 * 0), [o5_1] "n"((16 * (1 >> 1) + 4 * 1 + 2 * (1 & 1)) * ROW + 64 * 1), [o6_0] "n"((16 * (1 >> 1) + 4 * 2 + 2 * (1 & 1)) * ROW + 64 * 0), [o6_1] "n"((16 * (1 >> 1) + 4 * 2 + 2 * (1 & 1)) * ROW + 64 * 1), [o7_0] "n"((16 * (1 >> 1) + 4 * 3 + 2 * (1 & 1)) * ROW + 64 * 0), [o7_1] "n"((16 * (1 >> 1) + 4 * 3 + 2 * (1 & 1)) * ROW + 64 * 1), [o8_0] "n"((16 * (2 >> 1) + 4 * 0 + 2 * (2 & 1)) * ROW + 64 * 0), [o8_1] "n"((16 * (2 >> 1) + 4 * 0 + 2 * (2 & 1)) * ROW + 64 * 1), [o9_0] "n"((16 * (2 >> 1) + 4 * 1 + 2 * (2 & 1)) * ROW + 64 * 0), [o9_1] "n"((16 * (2 >> 1) + 4 * 1 + 2 * (2 & 1)) * ROW + 64 * 1), [o10_0] "n"((16 * (2 >> 1) + 4 * 2 + 2 * (2 & 1)) * ROW + 64 * 0), [o10_1] "n"((16 * (2 >> 1) + 4 * 2 + 2 * (2 & 1)) * ROW + 64 * 1), [o11_0] "n"((16 * (2 >> 1) + 4 * 3 + 2 * (2 & 1)) * ROW + 64 * 0), [o11_1] "n"((16 * (2 >> 1) + 4 * 3 + 2 * (2 & 1)) * ROW + 64 * 1), [o12_0] "n"((16 * (3 >> 1) + 4 * 0 + 2 * (3 & 1)) * ROW + 64 * 0), [o12_1] "n"((16 * (3 >> 1) + 4 * 0 + 2 * (3 & 1)) * ROW + 64 * 1), [o13_0] "n"((16 * (3 >> 1) + 4 * 1 + 2 * (3 & 1)) * ROW + 64 * 0), [o13_1] "n"((16 * (3 >> 1) + 4 * 1 + 2 * (3 & 1)) * ROW + 64 * 1), [o14_0] "n"((16 * (3 >> 1) + 4 * 2 + 2 * (3 & 1)) * ROW + 64 * 0), [o14_1] "n"((16 * (3 >> 1) + 4 * 2 + 2 * (3 & 1)) * ROW + 64 * 1), [o15_0] "n"((16 * (3 >> 1) + 4 * 3 + 2 * (3 & 1)) * ROW + 64 * 0), [o15_1] "n"((16 * (3 >> 1) + 4 * 3 + 2 * (3 & 1)) * ROW + 64 * 1)
+            : "scc", "memory");
+    }
+}
+
 template <int D> struct DqSmem {
     unsigned char k[NB][p16_tile_bytes(D)];   // 4 x 17 KB (D = 128) or 4 x 9 KB
     unsigned char v[NB][p16_tile_bytes(D)];
@@ -167,6 +465,7 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
     uint32_t ktr_addr[2];
     ktr_addr[0] = lds_k + (4 * jj + hh) * P16_ROW_BYTES + 2 * (16 * grp2 + 4 * (j16 & 3));
     ktr_addr[1] = ktr_addr[0] + 2 * P16_TILE_BYTES;
+    const uint32_t kres_addr = lds_k + hh * P16_ROW_BYTES + 2 * l32;     // single K elements, for the residual path
 
     f32x16 dq[NDB];
 #pragma unroll
@@ -230,9 +529,10 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
 
     // Vector phase of a block: P^T = exp2(S^T c - LSE log2e), dS^T = P^T (dP^T - Delta), rounded to bf16
     // operand slots.  MASKED: the tile needs the causal mask (key positions from LDS).
+    // The lane's dS^T values of the block in fp32 (kept for the residual path) and the largest |dS| among them.
+    float ds[16], ds_max;
     auto v_phase = [&](int kpos_slot, int half, auto masked_c) __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked_c)::value;
-        float ds[16];
 #pragma unroll
         for (int x = 0; x < 16; ++x) {
             const float p = fast_exp2(fmaf(s[x], c_log2, neg_lse2));
@@ -251,6 +551,19 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
         }
         dsf[0] = pack_bf16x8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
         dsf[1] = pack_bf16x8(ds[8], ds[9], ds[10], ds[11], ds[12], ds[13], ds[14], ds[15]);
+        ds_max = 0.f;
+#pragma unroll
+        for (int x = 0; x < 16; x += 2) asm("v_max3_f32 %0, |%1|, |%2|, %0" : "+v"(ds_max) : "v"(ds[x]), "v"(ds[x + 1]));
+    };
+    // Blocks with a large |dS| add the residuals of the rounding (rare; the block's tile stays in LDS until both groups
+    // have passed the next matrix phase).  Called after the masked / unmasked variants of the vector phase have joined,
+    // so that the accumulators are not modified inside either branch.
+    auto v_phase_end = [&](int buf, int half) __attribute__((always_inline)) {
+        const f32x4 h0 = __builtin_bit_cast(f32x4, dsf[0]), h1 = __builtin_bit_cast(f32x4, dsf[1]);
+        const uint32_t hw[8] = {__float_as_uint(h0[0]), __float_as_uint(h0[1]), __float_as_uint(h0[2]), __float_as_uint(h0[3]),
+                                __float_as_uint(h1[0]), __float_as_uint(h1[1]), __float_as_uint(h1[2]), __float_as_uint(h1[3])};
+        dq_add_residuals<NDB, P16_ROW_BYTES>(dq, ds, hw, kres_addr + buf * P16_TILE_BYTES + 32 * half * P16_ROW_BYTES,
+                                            __builtin_amdgcn_ballot_w64(ds_max >= DS_SPLIT));
         // keep the whole vector phase on this side of the next barrier
         asm volatile("" : "+v"(dsf[0]), "+v"(dsf[1]));
     };
@@ -274,6 +587,7 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
         if ((blk & 1) == 0 && t + AHEAD < NT) fetch_tile(t + AHEAD);
         if (t >= n_full_g) v_phase(t & (2 * NB - 1), blk & 1, std::true_type{});
         else v_phase(t & (2 * NB - 1), blk & 1, std::false_type{});
+        v_phase_end(t & (NB - 1), blk & 1);
     };
 
     for (int j = 0; j < AHEAD && j < NT; ++j) fetch_tile(j);

@@ -2,15 +2,21 @@
 launch configuration bench.py times.
 
 The oracle cannot recompute a whole full-size shard, so:
-  (i)  o, lse and dq are row-local: sampled rows (first / last rows of every segment, rows around tile
-       boundaries, evenly spaced rows) x all local heads are recomputed one by one in fp64 against all
-       their visible keys and compared with the rows of the full GPU run;
-  (ii) dk, dv need every shard row, so they are compared in full on a q-SUB-SHARD run: the library is
-       called with a q range made of scattered short segments of the real shard (true offsets, true
-       chunk list, one GQA group taken as a strided view of the real tensors), for which the full
-       oracle is affordable; every dk/dv element of every chunk is compared;
-  (iii) properties that hold at any size tie the full-size dk, dv to the inputs:
-       sum_j dV_j = sum_i dO_i per kv head (rows of P sum to 1) and sum <q, dq> = sum <k, dk>.
+  (i)   o, lse and dq are row-local: at least 512 sampled (row, head subset) pairs -- the first / last rows of
+        every segment, rows around tile boundaries, half of the rest among the first 1024 rows of each segment
+        (the rows with the fewest visible keys and the most sharply peaked softmax), the others uniform over the
+        shard -- are recomputed in fp64 against all their visible keys and compared with the full GPU run;
+  (ii)  dk, dv need every shard row, so they are compared in full on a q-SUB-SHARD run: the library is called
+        with a q range made of scattered short segments of the real shard (true offsets, true chunk list, one
+        GQA group taken as a strided view of the real tensors), for which the full oracle is affordable;
+  (iii) dk, dv of the TIMED launch itself, element by element: the last keys of the shard's last segment are
+        visible to the last shard rows only, so the oracle over those rows x all heads gives the exact dk / dv of
+        those keys (all kv heads) as the full-size launch must have written them;
+  (iv)  the full launch of one remote chunk against other launches of the same kernel: the sum of the dk / dv of
+        a partition of the shard into two sub-shards (additivity over query rows), and the same launch with a
+        different head-run length (other workgroup shapes, XCD splits and atomics use), every element;
+  (v)   properties that hold at any size: sum_j dV_j = sum_i dO_i per kv head (rows of P sum to 1) and
+        sum <q, dq> = sum <k, dk>.
 """
 import numpy as np
 import pytest
@@ -23,21 +29,44 @@ from parity_util import check, chunk_slices, to64
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
-TRIPLE_BUDGET = 1.0e8   # (row, key, head) triples per oracle call: seconds to tens of seconds on 16 cores
+TRIPLE_BUDGET = 1.0e8   # (row, key, head) triples per oracle call of parts (ii) and (iii): about 15 s on 16 cores
+N_SAMPLED_ROWS = 512
 
 
 def _sample_rows(w, n_target):
+    """Structured rows of every segment, then half of the remainder from the first 1024 rows of each segment and
+    half uniformly over the shard.  Packed row indices, ascending."""
     rows, off = set(), 0
+    rng = np.random.default_rng(5)
+    early = []
     for s, n in w.q_segs:
-        for r in (0, 1, 63, 64, 127, 128, 129, n // 2, n - 129, n - 128, n - 2, n - 1):
+        for r in (0, 1, 31, 32, 63, 64, 127, 128, 129, 255, 256, 257, n // 2, n - 257, n - 256, n - 129, n - 128, n - 2, n - 1):
             if 0 <= r < n:
                 rows.add(off + r)
+        early.append(off + np.arange(min(n, 1024)))
         off += n
-    rng = np.random.default_rng(5)
-    lq = w.lq
-    extra = max(0, n_target - len(rows))
-    rows.update(int(x) for x in rng.choice(lq, size=extra, replace=False))
+    early = np.concatenate(early)
+    need = max(0, n_target - len(rows))
+    pool = np.setdiff1d(early, np.fromiter(rows, dtype=np.int64))
+    rows.update(int(x) for x in rng.choice(pool, size=min(len(pool), need // 2), replace=False))
+    pool = np.setdiff1d(np.arange(w.lq), np.fromiter(rows, dtype=np.int64))
+    rows.update(int(x) for x in rng.choice(pool, size=min(len(pool), max(0, n_target - len(rows))), replace=False))
     return np.array(sorted(rows), dtype=np.int64)
+
+
+def _kv_of(w, h):
+    return w.kv_of_q[h] if w.kv_of_q else h // (w.n_q_heads // w.n_kv_heads)
+
+
+def _locate(w, pos):
+    """(chunk index, packed row within the chunk) of the key at global position pos."""
+    for j, ch in enumerate(w.chunks):
+        r0 = 0
+        for s, n in ch:
+            if s <= pos < s + n:
+                return j, r0 + (pos - s)
+            r0 += n
+    raise ValueError(pos)
 
 
 @pytest.mark.parametrize("idx,head_dim", [(2, 128), (3, 128), (4, 128), (5, 128), (2, 64)])
@@ -56,7 +85,7 @@ def test_full_size_sampled_rows_subshard_and_properties(idx, head_dim):
     torch.cuda.synchronize()
     print("  GPU replay done", flush=True)
 
-    # (iii) properties at full size (fp64 sums on the GPU tensors)
+    # (v) properties at full size (fp64 sums on the GPU tensors)
     dv_sum = sum(x.double().sum(0) for x in run.dv)                      # [nkv, d]
     do_sum = run.d_o.double().sum(0).reshape(nkv, grp, d).sum(1)         # default head map: groups are contiguous
     rel = float((dv_sum - do_sum).norm() / do_sum.norm())
@@ -73,24 +102,45 @@ def test_full_size_sampled_rows_subshard_and_properties(idx, head_dim):
             assert not run.dk[j].any() and not run.dv[j].any()
     print(f"    {n_future} chunks wholly in the future: zero dk/dv", flush=True)
 
-    # (i) sampled rows of the full run
-    avg_keys = float(np.mean(q_pos_all + 1))
-    rows = _sample_rows(w, max(24, int(TRIPLE_BUDGET / (avg_keys * nq))))
-    q_pos = q_pos_all[rows]
-    n_keys = int(q_pos.max()) + 1
-    k64, v64 = to64(inputs["k"][:n_keys]), to64(inputs["v"][:n_keys])
-    kv_pos = np.arange(n_keys, dtype=np.int64)
-    print(f"  oracle on {len(rows)} sampled rows x {nq} heads x up to {n_keys} keys", flush=True)
-    ref = oracle.attn_bwd(to64(inputs["q"][rows]), q_pos, k64, v64, kv_pos, to64(inputs["d_o"][rows]), w.scale)
-    o_ref, lse_ref = oracle.attn_fwd(to64(inputs["q"][rows]), q_pos, k64, v64, kv_pos, w.scale)
-    rt = torch.as_tensor(rows, device=DEV)
-    check("o[rows]", run.o[rt].cpu(), o_ref, "bf16")
-    check("lse[rows]", run.lse[:, rt].cpu(), lse_ref, "bf16")
-    check("delta[rows]", run.delta[:, rt].cpu(), ref["delta"], "bf16", abs_factor=float(d) ** 0.5)
-    check("dq[rows]", run.dq[rt].cpu(), ref["dq"], "bf16")
-    del ref, o_ref
+    # (i) sampled (row, head subset) pairs of the full run, in groups of rows of similar position
+    rows = _sample_rows(w, N_SAMPLED_ROWS)
+    assert len(rows) >= N_SAMPLED_ROWS
+    rng = np.random.default_rng(17)
+    got = {n: [] for n in ("o", "lse", "delta", "dq")}
+    want = {n: [] for n in got}
+    n_pairs_checked = 0
+    groups = [rows[i:i + 64] for i in range(0, len(rows), 64)]
+    print(f"  oracle on {len(rows)} sampled rows in {len(groups)} groups, 1-2 heads each", flush=True)
+    for g_rows in groups:
+        q_pos = q_pos_all[g_rows]
+        n_keys = int(q_pos.max()) + 1
+        n_h = 2 if n_keys <= 200 * 1024 else 1       # rows that see several hundred thousand keys: one head each
+        heads = sorted(int(h) for h in rng.choice(nq, size=min(n_h, nq), replace=False))
+        kvs = sorted({_kv_of(w, h) for h in heads})
+        kv_map = [kvs.index(_kv_of(w, h)) for h in heads]
+        k64, v64 = to64(inputs["k"][:n_keys][:, kvs]), to64(inputs["v"][:n_keys][:, kvs])
+        q64, g64 = to64(inputs["q"][g_rows][:, heads]), to64(inputs["d_o"][g_rows][:, heads])
+        kv_pos = np.arange(n_keys, dtype=np.int64)
+        ref = oracle.attn_bwd(q64, q_pos, k64, v64, kv_pos, g64, w.scale, kv_map)
+        o_ref, _ = oracle.attn_fwd(q64, q_pos, k64, v64, kv_pos, w.scale, kv_map)
+        rt, ht = torch.as_tensor(g_rows, device=DEV), torch.as_tensor(heads, device=DEV)
+        got["o"].append(run.o[rt][:, ht].cpu().numpy()); want["o"].append(o_ref)
+        got["dq"].append(run.dq[rt][:, ht].cpu().numpy()); want["dq"].append(ref["dq"])
+        got["lse"].append(run.lse[ht][:, rt].cpu().numpy().T); want["lse"].append(ref["lse"].T)
+        got["delta"].append(run.delta[ht][:, rt].cpu().numpy().T); want["delta"].append(ref["delta"].T)
+        n_pairs_checked += len(g_rows) * len(heads)
+        del ref, o_ref, k64, v64
+    print(f"    {n_pairs_checked} (row, head) pairs", flush=True)
+    cat = lambda xs: np.concatenate([np.asarray(x).reshape(-1) for x in xs])
+    check("o[rows]", cat(got["o"]), cat(want["o"]), "bf16")
+    check("lse[rows]", cat(got["lse"]), cat(want["lse"]), "bf16")
+    check("dq[rows]", cat(got["dq"]), cat(want["dq"]), "bf16")
+    # Delta is an intermediate, not one of the five outputs: a sum of d products of dO with o, so its absolute error
+    # is up to sqrt(d) |dO| times that of o; its effect is covered by the flat bounds on dq above and dk below
+    check("delta[rows] (intermediate)", cat(got["delta"]), cat(want["delta"]), "bf16", abs_factor=float(d) ** 0.5)
 
     # (ii) q-sub-shard run: scattered 16-row segments of the real shard, one GQA group (strided views)
+    avg_keys = float(np.mean(q_pos_all + 1))
     n_rows = int(min(192, max(32, TRIPLE_BUDGET / (avg_keys * grp))))
     n_seg = max(2, min(12, n_rows // 16))
     rng = np.random.default_rng(9)
@@ -98,14 +148,20 @@ def test_full_size_sampled_rows_subshard_and_properties(idx, head_dim):
     starts = sorted(int(x) for x in rng.choice(lq // 16 - 1, size=n_seg - 2, replace=False) * 16 + 3) if n_seg > 2 else []
     starts = sorted(set([0] + starts + [lq - 16]))
     sub_rows = np.concatenate([np.arange(s, s + 16) for s in starts])
-    # packed rows -> global segments (a 16-row run may straddle two shard segments; split it then)
+
+    def segments_of(packed_rows):
+        """packed shard rows (ascending) -> global segments (a run may straddle two shard segments; split it then)"""
+        pos = q_pos_all[packed_rows]
+        segs, s0 = [], 0
+        for i in range(1, len(pos) + 1):
+            if i == len(pos) or pos[i] != pos[i - 1] + 1:
+                segs.append((int(pos[s0]), i - s0))
+                s0 = i
+        assert len(segs) <= hexi.HEXI_MAX_SEGS
+        return segs
+
     sub_pos = q_pos_all[sub_rows]
-    segs, s0 = [], 0
-    for i in range(1, len(sub_pos) + 1):
-        if i == len(sub_pos) or sub_pos[i] != sub_pos[i - 1] + 1:
-            segs.append((int(sub_pos[s0]), i - s0))
-            s0 = i
-    assert len(segs) <= hexi.HEXI_MAX_SEGS
+    segs = segments_of(sub_rows)
     st = torch.as_tensor(sub_rows, device=DEV)
     q_sub = run.q[st][:, :grp]            # strided view: first group's q heads
     do_sub = run.d_o[st][:, :grp]
@@ -142,3 +198,59 @@ def test_full_size_sampled_rows_subshard_and_properties(idx, head_dim):
     dv_ref = np.concatenate([chunk_slices(w, j, ref["dv"], n_keys) for j in range(len(w.chunks))])
     check("sub.dk (all keys)", dk_all, dk_ref, "bf16")
     check("sub.dv (all keys)", dv_all, dv_ref, "bf16")
+    del ref, dk_all, dv_all, dk_ref, dv_ref, dks, dvs
+
+    # (iii) dk / dv of the timed launch: the last n keys of the shard's last segment see only the last n shard rows
+    p_end = int(q_pos_all.max()) + 1
+    n_last = int(max(8, min(128, TRIPLE_BUDGET * 0.75 / (float(p_end) * nq))))
+    last_rows = np.arange(lq - n_last, lq)
+    assert q_pos_all[last_rows[0]] == p_end - n_last          # the shard's last segment is at least n_last long
+    print(f"  oracle on the last {n_last} shard rows x all {nq} heads x {p_end} keys (dk / dv of the last {n_last} keys)", flush=True)
+    ref = oracle.attn_bwd(to64(inputs["q"][last_rows]), q_pos_all[last_rows], to64(inputs["k"][:p_end]), to64(inputs["v"][:p_end]),
+                          np.arange(p_end, dtype=np.int64), to64(inputs["d_o"][last_rows]), w.scale, w.kv_of_q)
+    j_diag, r_first = _locate(w, p_end - n_last)
+    assert _locate(w, p_end - 1) == (j_diag, r_first + n_last - 1)
+    check("dk[last keys] (timed launch)", run.dk[j_diag][r_first:r_first + n_last].cpu(), ref["dk"][p_end - n_last:], "bf16")
+    check("dv[last keys] (timed launch)", run.dv[j_diag][r_first:r_first + n_last].cpu(), ref["dv"][p_end - n_last:], "bf16")
+    del ref
+
+    # (iv) one remote chunk: full launch = sum of the launches of two sub-shards (the scattered rows of (ii), all
+    # heads, and the rest of the shard), and = the same launch with another head-run length.  fp32 summation order
+    # is all that differs, so the bounds are far below the output tolerance.
+    def remote(ch):
+        return not any(ks < qs + qn and qs < ks + kn for qs, qn in w.q_segs for ks, kn in ch) and ch[0][0] <= q_pos_all.max()
+    j_r = next(j for j, ch in enumerate(w.chunks) if remote(ch))
+    kc, vc = run.k[j_r], run.v[j_r]
+    dk_full, dv_full = run.dk[j_r], run.dv[j_r]
+    acc_k, acc_v = torch.zeros_like(dk_full), torch.zeros_like(dv_full)
+    rest = np.setdiff1d(np.arange(lq), sub_rows)
+    for part in (sub_rows, rest):
+        pt = torch.as_tensor(part, device=DEV)
+        q_p, do_p = run.q[pt].contiguous(), run.d_o[pt].contiguous()
+        lse_p, delta_p = run.lse[:, pt].contiguous(), run.delta[:, pt].contiguous()
+        hexi.hexi_attn_bwd_chunk(hexi.desc_for(q_p, kc, w.scale, w.kv_of_q), segments_of(part), w.chunks[j_r], q_p, kc, vc, None, do_p,
+                                 lse_p, delta_p, None, acc_k, acc_v, flags=hexi.HEXI_ACCUMULATE | hexi.HEXI_SKIP_DQ)
+    torch.cuda.synchronize()
+
+    def close(name, a, b):
+        err = float((a.double() - b.double()).abs().max())
+        rel = float((a.double() - b.double()).norm() / b.double().norm())
+        print(f"    {name}: max_abs={err:.3e} rel_l2={rel:.3e}", flush=True)
+        assert err <= 2e-3 and rel <= 1e-4, name
+
+    print(f"  chunk {j_r}: full launch vs the sum over two sub-shards ({len(sub_rows)} + {len(rest)} rows)", flush=True)
+    close("dk additivity", acc_k, dk_full)
+    close("dv additivity", acc_v, dv_full)
+    del acc_k, acc_v
+    try:
+        for run_len in (1, grp):
+            dk2, dv2 = torch.empty_like(dk_full), torch.empty_like(dv_full)
+            hexi.hexi_set_dkdv_run_len(run_len)
+            hexi.hexi_attn_bwd_chunk(run.desc[j_r], w.q_segs, w.chunks[j_r], run.q, kc, vc, None, run.d_o, run.lse, run.delta,
+                                     None, dk2, dv2, flags=hexi.HEXI_SKIP_DQ)
+            torch.cuda.synchronize()
+            close(f"dk, head runs of {run_len}", dk2, dk_full)
+            close(f"dv, head runs of {run_len}", dv2, dv_full)
+            del dk2, dv2
+    finally:
+        hexi.hexi_set_dkdv_run_len(0)

@@ -25,9 +25,10 @@ def force_run_len():
     hexi.hexi_set_dkdv_run_len(0)
 
 
-def _run_and_compare(w, seed=20260507, fused=True, grad_abs_factor=1.0):
-    """Runs the whole replay on the GPU and compares every element of every output with the oracle.
-    `grad_abs_factor` widens only the max-abs bound of dq/dk (see test_tier1_minis_full_tensor)."""
+def _run_and_compare(w, seed=20260507, fused=True):
+    """Runs the whole replay on the GPU and compares every element of every output with the oracle at the flat
+    tolerances.  (Delta, an intermediate and not one of the five outputs, is a sum of d products of dO with o: its
+    max-abs bound is that of o times sqrt(d); its effect on the outputs is covered by the flat bounds on dq / dk.)"""
     print(f"\n[{w.name}] lq={w.lq} heads={w.n_q_heads}/{w.n_kv_heads} d={w.head_dim} chunks={len(w.chunks)} fused={fused}", flush=True)
     inputs = wl.make_inputs(w, seed)
     run = replay.ShardRun(w, inputs, DEV, fused_merge=fused)
@@ -41,7 +42,7 @@ def _run_and_compare(w, seed=20260507, fused=True, grad_abs_factor=1.0):
     failures = []
     for name, got, want, fac in (("o", run.o.cpu(), ref["o"], 1.0), ("lse", run.lse.cpu(), ref["lse"], 1.0),
                                  ("delta", run.delta.cpu(), ref["delta"], float(w.head_dim) ** 0.5),
-                                 ("dq", run.dq.cpu(), ref["dq"], grad_abs_factor), ("dk", dk, dk_ref, grad_abs_factor),
+                                 ("dq", run.dq.cpu(), ref["dq"], 1.0), ("dk", dk, dk_ref, 1.0),
                                  ("dv", dv, dv_ref, 1.0)):
         try:
             check(name, got, want, w.dtype, abs_factor=fac)
@@ -80,14 +81,9 @@ def test_cfg1_unfused_partials_and_merge():
 
 @pytest.mark.parametrize("idx,shrink", [(2, 16), (3, 16), (4, 32), (5, 32)])
 def test_tier1_minis_full_tensor(idx, shrink):
-    w = wl.config(idx, shrink=shrink)
-    # dQ = scale * dS K and dK = scale * dS^T Q are linear in the operand that configuration 4 scales
-    # by 3, and the mini puts its rows 32x closer to the start of the sequence than the real shard
-    # (softmax over ~1.5K instead of ~48K keys of exp(3 z) weights: one or two keys dominate a row).
-    # The bf16 rounding of dS (relative 2^-9) then shows up 3x larger in absolute terms; the max-abs
-    # bound of dq/dk is widened by k_scale for this mini only.  The full-size configuration is held
-    # to the unscaled bound in test_gpu_fullsize.py.
-    _run_and_compare(w, grad_abs_factor=w.k_scale)
+    # (configuration 4 scales K by 3: sharply peaked rows, whose few large dS values the dQ kernel carries with
+    # their rounding residuals; every configuration is held to the same flat bounds)
+    _run_and_compare(wl.config(idx, shrink=shrink))
 
 
 def test_cfg2_mini_unfused_and_contiguous_chunking_agree():
@@ -368,8 +364,7 @@ def test_forward_exact_softmax_fallback(d):
         print(f"  scales {first_scale}/{later_scale}: lse range {np.min(lse_ref):.1f} .. {np.max(lse_ref):.1f}", flush=True)
         assert spread > 50.0     # the case really spans a wide range
         check("o", o.cpu(), o_ref, "bf16")
-        # lse values reach the hundreds here: the absolute bound scales with them (fp32 has 24 bits)
-        check("lse", lse.cpu(), lse_ref, "bf16", abs_factor=max(1.0, float(np.max(np.abs(lse_ref))) * 1e-2))
+        check("lse", lse.cpu(), lse_ref, "bf16")     # values in the hundreds, still inside the flat bound
 
 
 def test_device_share_of_a_scheduled_plan():
