@@ -28,12 +28,25 @@ Readings where the paper is silent or at odds with itself:
      baseline layouts (singletons = Ring, one group = Ulysses, equal consecutive groups of every divisor
      size = USP meshes) are always candidates; ranking by the smallest intra-group edge bandwidth (a group
      of one counts as infinitely fast), ties by fewer groups, then by first appearance.
+ r4b Stage I super-node abstraction (Alg. 1 line 2): a group G_k of a retained partition is summarised by
+     C_k = sum c_d, Bw_k = sum b_d, its memory proxy min_d (m_d - M_static_d) (the activation budget of its tightest
+     device), its size, the mean startup latency and mean inverse bandwidth over its ordered intra-group device pairs
+     (both 0 for a group of one), and the same two means over the edges u -> d from its ring predecessor's devices to
+     its own (the inter-group edges that carry its ring traffic).  Stage II sees only these summaries: a group-level
+     plan (L_1..L_K) is priced as if every group were one device that splits its tokens and heads evenly,
+         T_nonattn = max_k max(72 B L_k H^2 / C_k, 40 B L_k H P / Bw_k),
+         T_A2A     = max_k 4 (alpha_k + beta_k 3 B (L_k / |G_k|) ((N / |G_k|) d_h) P)       (0 for |G_k| = 1),
+         T_step(t) = max_k max(16 B L_k L_src(t) (N d_h) / C_k,  [t > 0] alpha'_k + beta'_k 4 B L_src(t) ((N / |G_k|) d_h) P),
+     and kept only if B P (gamma (L_k / |G_k|) H + 2 L_k (N / |G_k|) d_h) fits every group's memory proxy.  On a
+     cluster of identical devices with identical links this equals the full model of the even schedule.
  r5  Stage II seeds: uniform (L_k proportional to the group's device count: the symmetric baselines),
      compute-proportional, square-root-compute, memory-capped (compute-proportional, groups clipped to the
      L their memory proxy admits under an even split of tokens and heads, the excess going to the others in
-     proportion to compute); perturbations: `perturb` = 1/32 of L_tot moved between ring-adjacent groups, both
-     directions.  Lengths are multiples of the token quantum q (largest-remainder rounding).  Scored with the
-     default rank-level assignment; the best M2 of each partition go on.
+     proportion to compute; a group's cap is the largest multiple of q not above budget / bytes-per-token, i.e.
+     floor(x / q) q evaluated in floating point); perturbations: `perturb` = 1/32 of L_tot moved between
+     ring-adjacent groups, both directions.  Lengths are multiples of the token quantum q (largest-remainder
+     rounding).  Scored on the super-node summaries (r4b); the best M2 of each partition go on, and a plan whose
+     initial rank-level assignment (r6) fails the per-device memory filter is dropped there.
  r6  Stage III initial assignment: s_d and n_d proportional to c_d within the group (uniform for the
      uniform seed), largest-remainder rounding, ties to the lower device index.  Candidate pairs: ordered
      pairs of distinct devices in the same or ring-adjacent groups, lexicographic.  Moves per pair, in this
@@ -237,6 +250,72 @@ def partition_topology(cl, m1=64, gap_ratio=4.0):
     return [[list(g) for g in c[0]] for c in keep]
 
 
+class SuperNode:
+    """Stage I summary of one A2A group (reading r4b)."""
+    def __init__(self, size, compute, mem_bw, mem, alpha_in, beta_in, alpha_ring, beta_ring):
+        self.size, self.compute, self.mem_bw, self.mem = size, compute, mem_bw, mem
+        self.alpha_in, self.beta_in = alpha_in, beta_in            # mean over ordered intra-group pairs
+        self.alpha_ring, self.beta_ring = alpha_ring, beta_ring    # mean over edges predecessor group -> this group
+
+
+def abstract_super_nodes(cl, groups):
+    K = len(groups)
+    nodes = []
+    for k, g in enumerate(groups):
+        a_in = b_in = 0.0
+        pairs = 0
+        for d in g:
+            for j in g:
+                if d != j:
+                    a_in += cl.alpha[d][j]
+                    b_in += 1.0 / cl.bw[d][j]
+                    pairs += 1
+        if pairs:
+            a_in, b_in = a_in / pairs, b_in / pairs
+        a_r = b_r = 0.0
+        if K > 1:
+            pred = groups[(k - 1) % K]
+            for u in pred:
+                for d in g:
+                    a_r += cl.alpha[u][d]
+                    b_r += 1.0 / cl.bw[u][d]
+            a_r, b_r = a_r / (len(pred) * len(g)), b_r / (len(pred) * len(g))
+        nodes.append(SuperNode(len(g), sum(cl.c[d] for d in g), sum(cl.b[d] for d in g),
+                               min(cl.m[d] - cl.m_static[d] for d in g), a_in, b_in, a_r, b_r))
+    return nodes
+
+
+def supernode_cost(nodes, mo, lens):
+    """Coarse T_blk of a group-level plan: every group one device, tokens and heads split evenly inside it."""
+    K = len(nodes)
+    nonattn = max(max(72.0 * mo.B * lens[k] * mo.H * mo.H / nodes[k].compute, 40.0 * mo.B * lens[k] * mo.H * mo.P / nodes[k].mem_bw)
+                  for k in range(K))
+    a2a = 0.0
+    for k, sn in enumerate(nodes):
+        if sn.size > 1:
+            vol = 3.0 * mo.B * (lens[k] / sn.size) * ((mo.N / sn.size) * mo.d_h) * mo.P
+            a2a = max(a2a, 4.0 * (sn.alpha_in + sn.beta_in * vol))
+    ring = 0.0
+    for t in range(K):
+        worst = 0.0
+        for k, sn in enumerate(nodes):
+            src = (k - t) % K
+            cost = 16.0 * mo.B * lens[k] * lens[src] * (mo.N * mo.d_h) / sn.compute
+            if t > 0:
+                msg = 4.0 * mo.B * lens[src] * ((mo.N / sn.size) * mo.d_h) * mo.P
+                cost = max(cost, sn.alpha_ring + sn.beta_ring * msg)
+            worst = max(worst, cost)
+        ring += worst
+    return nonattn + a2a + ring
+
+
+def supernode_feasible(nodes, mo, lens):
+    for k, sn in enumerate(nodes):
+        if mo.B * mo.P * (mo.gamma * (lens[k] / sn.size) * mo.H + 2.0 * lens[k] * ((mo.N / sn.size) * mo.d_h)) > sn.mem:
+            return False
+    return True
+
+
 def initialize_assignment(cl, mo, groups, l_group, uniform, q):
     s_pre, n_heads = [0] * cl.n, [0] * cl.n
     for k, g in enumerate(groups):
@@ -249,6 +328,8 @@ def initialize_assignment(cl, mo, groups, l_group, uniform, q):
 
 
 def generate_candidates(cl, mo, groups, q, perturb):
+    """Group-level plans of one partition, from the groups' aggregate compute and memory proxy (the super-node
+    summaries) alone: [(lens, uniform_flag), ...] in a fixed order."""
     K = len(groups)
     comp = [sum(cl.c[d] for d in g) for g in groups]
     seeds = []
@@ -355,13 +436,16 @@ def solve(cl, mo, m1=64, m2=16, i_max=100, gap_ratio=4.0, q=64, perturb=1.0 / 32
         move_tokens = max(1, mo.l_tot // (q * cl.n * 16)) * q
     best, best_c = None, INF
     for groups in partition_topology(cl, m1, gap_ratio):
+        nodes = abstract_super_nodes(cl, groups)
         scored = []
         for idx, (lens, uniform) in enumerate(generate_candidates(cl, mo, groups, q, perturb)):
-            T = initialize_assignment(cl, mo, groups, lens, uniform, q)
-            if feasible(cl, mo, T):
-                scored.append((t_blk(cl, mo, T), idx, T))
+            if supernode_feasible(nodes, mo, lens):
+                scored.append((supernode_cost(nodes, mo, lens), idx, lens, uniform))
         scored.sort(key=lambda x: (x[0], x[1]))
-        for _, _, T in scored[:m2]:
+        for _, _, lens, uniform in scored[:m2]:
+            T = initialize_assignment(cl, mo, groups, lens, uniform, q)
+            if not feasible(cl, mo, T):
+                continue
             T, C = refine(cl, mo, T, i_max, move_tokens)
             if C < best_c:
                 best, best_c = T, C

@@ -241,6 +241,84 @@ std::vector<Partition> partition_topology(const Cluster& cl, int m1, double gap_
     return out;
 }
 
+// Stage I, second half (Alg. 1 line 2): a group of a retained partition summarised as one super-node -- aggregate
+// compute and memory bandwidth, the activation budget of its tightest device, and mean link costs (startup latency,
+// inverse bandwidth) over its ordered intra-group pairs and over the edges from its ring predecessor's devices to its
+// own.  Stage II prices group-level plans on these summaries alone.
+struct SuperNode {
+    double size, compute, mem_bw, mem;
+    double alpha_in, beta_in, alpha_ring, beta_ring;
+};
+
+std::vector<SuperNode> abstract_super_nodes(const Cluster& cl, const Partition& groups)
+{
+    const int K = (int)groups.size();
+    std::vector<SuperNode> nodes(K);
+    for (int k = 0; k < K; ++k) {
+        const auto& g = groups[k];
+        SuperNode sn{(double)g.size(), 0.0, 0.0, INF, 0.0, 0.0, 0.0, 0.0};
+        int pairs = 0;
+        for (int d : g) {
+            sn.compute += cl.c[d];
+            sn.mem_bw += cl.b[d];
+            sn.mem = std::min(sn.mem, cl.m[d] - cl.m_static[d]);
+            for (int j : g)
+                if (d != j) { sn.alpha_in += cl.al(d, j); sn.beta_in += 1.0 / cl.w(d, j); ++pairs; }
+        }
+        if (pairs) { sn.alpha_in = sn.alpha_in / pairs; sn.beta_in = sn.beta_in / pairs; }
+        if (K > 1) {
+            const auto& pred = groups[(k - 1 + K) % K];
+            for (int u : pred)
+                for (int d : g) { sn.alpha_ring += cl.al(u, d); sn.beta_ring += 1.0 / cl.w(u, d); }
+            const double edges = (double)(pred.size() * g.size());
+            sn.alpha_ring = sn.alpha_ring / edges; sn.beta_ring = sn.beta_ring / edges;
+        }
+        nodes[k] = sn;
+    }
+    return nodes;
+}
+
+// Coarse T_blk of a group-level plan: every group one device that splits its tokens and heads evenly.
+double supernode_cost(const std::vector<SuperNode>& nodes, const Model& mo, const std::vector<long long>& lens)
+{
+    const int K = (int)nodes.size();
+    const double B = (double)mo.B, H = (double)mo.H, P = (double)mo.P, N = (double)mo.N, d_h = (double)mo.d_h;
+    double nonattn = 0.0, a2a = 0.0, ring = 0.0;
+    for (int k = 0; k < K; ++k) {
+        const double L = (double)lens[k];
+        const double t = std::max(72.0 * B * L * H * H / nodes[k].compute, 40.0 * B * L * H * P / nodes[k].mem_bw);
+        nonattn = k == 0 ? t : std::max(nonattn, t);
+        if (nodes[k].size > 1.0) {
+            const double vol = 3.0 * B * (L / nodes[k].size) * ((N / nodes[k].size) * d_h) * P;
+            a2a = std::max(a2a, 4.0 * (nodes[k].alpha_in + nodes[k].beta_in * vol));
+        }
+    }
+    for (int t = 0; t < K; ++t) {
+        double worst = 0.0;
+        for (int k = 0; k < K; ++k) {
+            const int src = ((k - t) % K + K) % K;
+            double cost = 16.0 * B * (double)lens[k] * (double)lens[src] * (N * d_h) / nodes[k].compute;
+            if (t > 0) {
+                const double msg = 4.0 * B * (double)lens[src] * ((N / nodes[k].size) * d_h) * P;
+                cost = std::max(cost, nodes[k].alpha_ring + nodes[k].beta_ring * msg);
+            }
+            worst = std::max(worst, cost);
+        }
+        ring += worst;
+    }
+    return nonattn + a2a + ring;
+}
+
+bool supernode_feasible(const std::vector<SuperNode>& nodes, const Model& mo, const std::vector<long long>& lens)
+{
+    for (size_t k = 0; k < nodes.size(); ++k) {
+        const double L = (double)lens[k];
+        if ((double)(mo.B * mo.P) * (mo.gamma * (L / nodes[k].size) * (double)mo.H + 2.0 * L * (((double)mo.N / nodes[k].size) * (double)mo.d_h)) > nodes[k].mem)
+            return false;
+    }
+    return true;
+}
+
 // Stage III initial assignment: s_d and n_d proportional to c_d within the group (uniform for the uniform seed).
 Sched initialize_assignment(const Cluster& cl, const Model& mo, const Partition& groups, const std::vector<long long>& l_group, bool uniform, long long q)
 {
@@ -508,15 +586,19 @@ HEXI_EXPORT int hexi_sched_solve(const hexi_cluster* cluster, const hexi_model* 
     // Stages I and II: the shortlist of (partition, group plan) starting points, in a fixed order
     std::vector<Sched> starts;
     for (const Partition& groups : partition_topology(cl, m1, gap_ratio)) {
-        struct Scored { double cost; int idx; Sched T; };
+        // Stage II on the partition's super-node summaries: the m2 cheapest group-level plans that fit the groups'
+        // memory proxies go on; a plan whose initial rank-level assignment fails the per-device filter is dropped
+        const auto nodes = abstract_super_nodes(cl, groups);
+        struct Scored { double cost; int idx; };
         std::vector<Scored> scored;
         const auto plans = generate_candidates(cl, mo, groups, q, perturb);
-        for (int i = 0; i < (int)plans.size(); ++i) {
-            Sched T = initialize_assignment(cl, mo, groups, plans[i].lens, plans[i].uniform, q);
-            if (feasible(cl, mo, T)) scored.push_back({t_blk(cl, mo, T), i, T});
-        }
+        for (int i = 0; i < (int)plans.size(); ++i)
+            if (supernode_feasible(nodes, mo, plans[i].lens)) scored.push_back({supernode_cost(nodes, mo, plans[i].lens), i});
         std::sort(scored.begin(), scored.end(), [](const Scored& x, const Scored& y) { return x.cost != y.cost ? x.cost < y.cost : x.idx < y.idx; });
-        for (int i = 0; i < (int)scored.size() && i < m2; ++i) starts.push_back(scored[i].T);
+        for (int i = 0; i < (int)scored.size() && i < m2; ++i) {
+            Sched T = initialize_assignment(cl, mo, groups, plans[scored[i].idx].lens, plans[scored[i].idx].uniform, q);
+            if (feasible(cl, mo, T)) starts.push_back(T);
+        }
     }
     // Stage III: the descents are independent of each other, so they run on the host's cores; the winner is
     // picked afterwards in shortlist order (first strictly smaller cost), so the result does not depend on timing
