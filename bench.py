@@ -20,9 +20,15 @@ import time
 import torch
 
 PEAK_BF16_TFLOPS = 2516.6     # MI355X dense bf16 MFMA peak: 256 CU x 2.4 GHz x 4096 flop/clk/CU
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# command (see profiles/); None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {"cfg2_3b_zigzag": 0.676e9}   # bwd_dkdv_bf16_kernel<128,false>: 496 MB fetched + 180 MB written
+# HBM bytes per launch of the dominant kernel (the dK/dV kernel on a remote chunk) from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs of `bench.py --workload N --only-headline --copy-calibration` (see profiles/): fetched + written,
+# each scaled by what the same counter reads for a 1 GiB device copy.
+MEASURED_TRAFFIC_BYTES = {
+    "cfg2_3b_zigzag": 0.676e9,    # <128, false>: 496 MB fetched + 180 MB written
+    "cfg3_8b_asym": 1.18e9,       # <128, true>, the 12K-key chunk: 1020 MB + 160 MB
+    "cfg4_8b_long": 3.22e9,       # <128, true>: 2480 MB + 738 MB
+    "cfg5_70b_hp": 1.61e9,        # <128, true>: 1241 MB + 369 MB
+}
 
 
 def parse():

@@ -30,7 +30,7 @@ constexpr int WG_ROWS = 256;       // q rows per workgroup
 constexpr int AHEAD = 3;           // tile j + 3 is requested during tile j
 constexpr float LOG2E = 1.4426950408889634f;
 
-// A 32-key block in which some |dS| reaches this value also accumulates the residuals dS - bf16(dS) of the rounding:
+// A 32-key block in which some |bf16(dS)| reaches this value also accumulates the residuals dS - bf16(dS) of the rounding:
 // rounding dS to bf16 costs up to 2^-9 |dS| scale |k| per element of dQ, which for the few keys that dominate a
 // sharply peaked row (|dS| of several units) is most of the output tolerance.
 constexpr float DS_SPLIT = 2.0f;
@@ -529,8 +529,8 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
 
     // Vector phase of a block: P^T = exp2(S^T c - LSE log2e), dS^T = P^T (dP^T - Delta), rounded to bf16
     // operand slots.  MASKED: the tile needs the causal mask (key positions from LDS).
-    // The lane's dS^T values of the block in fp32 (kept for the residual path) and the largest |dS| among them.
-    float ds[16], ds_max;
+    // The lane's dS^T values of the block in fp32, kept for the residual path.
+    float ds[16];
     auto v_phase = [&](int kpos_slot, int half, auto masked_c) __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked_c)::value;
 #pragma unroll
@@ -551,9 +551,6 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
         }
         dsf[0] = pack_bf16x8(ds[0], ds[1], ds[2], ds[3], ds[4], ds[5], ds[6], ds[7]);
         dsf[1] = pack_bf16x8(ds[8], ds[9], ds[10], ds[11], ds[12], ds[13], ds[14], ds[15]);
-        ds_max = 0.f;
-#pragma unroll
-        for (int x = 0; x < 16; x += 2) asm("v_max3_f32 %0, |%1|, |%2|, %0" : "+v"(ds_max) : "v"(ds[x]), "v"(ds[x + 1]));
     };
     // Blocks with a large |dS| add the residuals of the rounding (rare; the block's tile stays in LDS until both groups
     // have passed the next matrix phase).  Called after the masked / unmasked variants of the vector phase have joined,
@@ -562,8 +559,11 @@ __global__ void __launch_bounds__(512) bwd_dq_bf16_kernel(const BwdArgs a, const
         const f32x4 h0 = __builtin_bit_cast(f32x4, dsf[0]), h1 = __builtin_bit_cast(f32x4, dsf[1]);
         const uint32_t hw[8] = {__float_as_uint(h0[0]), __float_as_uint(h0[1]), __float_as_uint(h0[2]), __float_as_uint(h0[3]),
                                 __float_as_uint(h1[0]), __float_as_uint(h1[1]), __float_as_uint(h1[2]), __float_as_uint(h1[3])};
+        // |x| >= 2 for a bf16 x is bit 14 of its pattern (the exponent's top bit): one test over the OR of the packed pairs
+        static_assert(DS_SPLIT == 2.0f, "the test below is bit 14 of the bf16 pattern");
+        const uint32_t any_bits = hw[0] | hw[1] | hw[2] | hw[3] | hw[4] | hw[5] | hw[6] | hw[7];
         dq_add_residuals<NDB, P16_ROW_BYTES>(dq, ds, hw, kres_addr + buf * P16_TILE_BYTES + 32 * half * P16_ROW_BYTES,
-                                            __builtin_amdgcn_ballot_w64(ds_max >= DS_SPLIT));
+                                            __builtin_amdgcn_ballot_w64((any_bits & 0x40004000u) != 0u));
         // keep the whole vector phase on this side of the next barrier
         asm volatile("" : "+v"(dsf[0]), "+v"(dsf[1]));
     };
