@@ -33,6 +33,8 @@ class Workload:
     k_scale: float = 1.0            # K is multiplied by this before rounding to dtype
     kv_of_q: Optional[List[int]] = None  # None: q head h reads kv head h // (nq / nkv)
     note: str = ""
+    q_head_ids: Optional[List[int]] = None   # global id of every local q head (None: the local index); only the
+    kv_head_ids: Optional[List[int]] = None  # synthetic values depend on it: a head's values follow it across shards
 
     @property
     def lq(self):
@@ -120,7 +122,8 @@ def from_schedule(groups, l_group, n_heads, device: int, head_dim: int = 128, q_
     kv_of_q = [kv_global.index(h // q_per_kv) for h in q_heads]
     chunks = [[(starts[(k - t) % len(groups)], l_group[(k - t) % len(groups)])] for t in range(len(groups))]
     return Workload(f"sched_dev{device}", dtype, len(q_heads), len(kv_global), head_dim, sum(l_group), [(starts[k], l_group[k])], chunks,
-                    kv_of_q=kv_of_q, note=f"device {device} of a scheduled plan: group {k} of {len(groups)}, q heads {lo}..{lo + len(q_heads) - 1}")
+                    kv_of_q=kv_of_q, note=f"device {device} of a scheduled plan: group {k} of {len(groups)}, q heads {lo}..{lo + len(q_heads) - 1}",
+                    q_head_ids=q_heads, kv_head_ids=kv_global)
 
 
 def contiguous_chunks(w: Workload, n_chunks: int) -> Workload:
@@ -130,24 +133,73 @@ def contiguous_chunks(w: Workload, n_chunks: int) -> Workload:
     return replace(w, name=w.name + "_contig", chunks=[[(j * lc, lc)] for j in range(n_chunks)])
 
 
-def _randn(shape, seed, tensor_id, block_rows=1 << 16):
-    g = torch.Generator().manual_seed(seed * 16 + tensor_id)
-    return torch.randn(shape, generator=g, dtype=torch.float32)
+VALUE_BLOCK = 1024     # tokens per independently seeded block of a synthetic tensor
+_M64 = (1 << 64) - 1
+
+
+def _block_seed(seed: int, tensor_id: int, block: int, head: int) -> int:
+    """A 63-bit generator seed that is a fixed function of (run seed, tensor, token block, global head)."""
+    x = (seed * 0x9E3779B97F4A7C15 + (tensor_id + 1) * 0xBF58476D1CE4E5B9 + (block + 1) * 0x94D049BB133111EB + (head + 1) * 0xD6E8FEB86659FD93) & _M64
+    x ^= x >> 30
+    x = (x * 0xBF58476D1CE4E5B9) & _M64
+    x ^= x >> 27
+    x = (x * 0x94D049BB133111EB) & _M64
+    x ^= x >> 31
+    return x & ((1 << 63) - 1)
+
+
+def global_rows(seed: int, tensor_id: int, head_ids: List[int], head_dim: int, segs: List[Seg], dtype, scale: float = 1.0) -> torch.Tensor:
+    """Rows of the synthetic global tensor [token, global head, d] for the token ranges `segs` and the heads
+    `head_ids`, packed back to back: [rows, len(head_ids), d] in `dtype`.  The values are N(0,1) (times `scale`,
+    then rounded to nearest even), drawn per (block of VALUE_BLOCK tokens, head) from a torch CPU generator whose seed
+    is a function of (seed, tensor, block, head) alone: every shard of one sequence, whatever its token range and head
+    subset, sees the same value at the same (token, head, column)."""
+    total = sum(n for _, n in segs)
+    out = torch.empty((total, len(head_ids), head_dim), dtype=dtype)
+    pieces = []          # (first output row, block, first and last+1 token of the block taken)
+    r0 = 0
+    for s0, n in segs:
+        pos = s0
+        while pos < s0 + n:
+            b = pos // VALUE_BLOCK
+            lo = pos - b * VALUE_BLOCK
+            hi = min(VALUE_BLOCK, s0 + n - b * VALUE_BLOCK)
+            pieces.append((r0, b, lo, hi))
+            r0 += hi - lo
+            pos += hi - lo
+
+    def fill(piece):
+        row, b, lo, hi = piece
+        g = torch.Generator()
+        for i, h in enumerate(head_ids):
+            g.manual_seed(_block_seed(seed, tensor_id, b, int(h)))
+            blk = torch.randn((VALUE_BLOCK, head_dim), generator=g, dtype=torch.float32)[lo:hi]
+            if scale != 1.0:
+                blk = blk * scale
+            out[row:row + (hi - lo), i] = blk.to(dtype)
+
+    if len(pieces) >= 16:      # the pieces write disjoint rows: a few host threads share them
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=8) as ex:
+            list(ex.map(fill, pieces))
+    else:
+        for piece in pieces:
+            fill(piece)
+    return out
 
 
 def make_inputs(w: Workload, seed: int = 20260507):
-    """q, d_o: [Lq, nq, d]; k, v: [l_tot, nkv, d] in GLOBAL token order -- CPU tensors of w's dtype.
+    """q, d_o: [Lq, nq, d] (the shard's rows); k, v: [l_tot, nkv, d] in GLOBAL token order -- CPU tensors of w's dtype.
 
-    Each tensor is N(0,1) from its own torch CPU generator seeded by (seed, tensor id), then K is
-    scaled by w.k_scale, then everything is rounded (nearest-even) to the workload dtype."""
+    Every tensor is a slice of a synthetic global tensor (see global_rows): N(0,1), K scaled by w.k_scale, rounded
+    (nearest-even) to the workload dtype."""
     dt = w.torch_dtype
-    q = _randn((w.lq, w.n_q_heads, w.head_dim), seed, TENSOR_IDS["q"]).to(dt)
-    d_o = _randn((w.lq, w.n_q_heads, w.head_dim), seed, TENSOR_IDS["d_o"]).to(dt)
-    k = _randn((w.l_tot, w.n_kv_heads, w.head_dim), seed, TENSOR_IDS["k"])
-    if w.k_scale != 1.0:
-        k.mul_(w.k_scale)
-    k = k.to(dt)
-    v = _randn((w.l_tot, w.n_kv_heads, w.head_dim), seed, TENSOR_IDS["v"]).to(dt)
+    q_ids = w.q_head_ids if w.q_head_ids is not None else list(range(w.n_q_heads))
+    kv_ids = w.kv_head_ids if w.kv_head_ids is not None else list(range(w.n_kv_heads))
+    q = global_rows(seed, TENSOR_IDS["q"], q_ids, w.head_dim, w.q_segs, dt)
+    d_o = global_rows(seed, TENSOR_IDS["d_o"], q_ids, w.head_dim, w.q_segs, dt)
+    k = global_rows(seed, TENSOR_IDS["k"], kv_ids, w.head_dim, [(0, w.l_tot)], dt, scale=w.k_scale)
+    v = global_rows(seed, TENSOR_IDS["v"], kv_ids, w.head_dim, [(0, w.l_tot)], dt)
     return dict(q=q, k=k, v=v, d_o=d_o)
 
 

@@ -168,6 +168,28 @@ def test_workload_geometry():
     assert all((x[n] == y[n]).all() for n in x) and x["q"].shape == (128, 4, 64)
 
 
+def test_synthetic_values_are_slices_of_one_global_tensor():
+    """A value depends only on (seed, tensor, token, global head, column): every shard of a sequence, whatever its token
+    range and head subset, sees the same q / k / v / dO at the same place (so the devices of one plan are consistent)."""
+    import torch
+    full = wl.global_rows(7, wl.TENSOR_IDS["q"], list(range(6)), 64, [(0, 5000)], torch.float32)
+    part = wl.global_rows(7, wl.TENSOR_IDS["q"], [4, 1], 64, [(1000, 37), (2040, 1100), (4999, 1)], torch.float32)
+    assert torch.equal(part[:37], full[1000:1037][:, [4, 1]])
+    assert torch.equal(part[37:1137], full[2040:3140][:, [4, 1]]) and torch.equal(part[1137:], full[4999:][:, [4, 1]])
+    assert not torch.equal(wl.global_rows(7, wl.TENSOR_IDS["k"], [0], 64, [(0, 64)], torch.float32), full[:64, :1])     # another tensor
+    assert not torch.equal(wl.global_rows(8, wl.TENSOR_IDS["q"], [0], 64, [(0, 64)], torch.float32), full[:64, :1])     # another seed
+    assert abs(float(full.std()) - 1.0) < 0.01 and abs(float(full.mean())) < 0.01
+    # two devices of one scheduled plan: common kv heads carry the same K, and a device's q rows are its block of the sequence
+    groups, l_group, n_heads = [[0, 1], [2, 3]], [1536, 2560], [2, 1, 1, 2]
+    w1 = wl.from_schedule(groups, l_group, n_heads, 1, head_dim=64, q_per_kv=2)
+    w3 = wl.from_schedule(groups, l_group, n_heads, 3, head_dim=64, q_per_kv=2)
+    assert (w1.q_head_ids, w1.kv_head_ids, w3.q_head_ids, w3.kv_head_ids) == ([2], [1], [1, 2], [0, 1])
+    x1, x3 = wl.make_inputs(w1, 3), wl.make_inputs(w3, 3)
+    assert torch.equal(x1["k"][:, 0], x3["k"][:, 1]) and torch.equal(x1["v"][:, 0], x3["v"][:, 1])
+    q_all = wl.global_rows(3, wl.TENSOR_IDS["q"], [0, 1, 2], 64, [(0, 4096)], torch.bfloat16)
+    assert torch.equal(x1["q"], q_all[:1536][:, [2]]) and torch.equal(x3["q"], q_all[1536:][:, [1, 2]])
+
+
 def test_a2a_argument_validation_without_gpu():
     """hexi_a2a_pack / hexi_a2a_unpack check their tables on the host before anything is launched."""
     lib = hexi.load()
