@@ -243,6 +243,34 @@ def test_strided_inputs_and_accumulate_flags(run_len, force_run_len):
     check("dv", torch.cat(dvs).cpu().numpy() + 0.25, ref["dv"], "bf16")
 
 
+@pytest.mark.parametrize("d", [128, 64])
+def test_dq_residuals_of_large_ds(d):
+    # The dQ kernel adds the rounding residuals of a 32-key block's dS when some |dS| >= 2.  With dO scaled by 64 (exact
+    # in bf16; every gradient is linear in dO) nearly every block takes that path -- masked and unmasked tiles, ragged
+    # tails, both groups of a workgroup -- and dq / 64 must still match the oracle, more closely than without the scaling
+    # (dS carried to fp32 accuracy instead of bf16); dk and dv, which have no such path, must come out as exactly 64 x
+    # their unscaled values.
+    w = _custom(f"residual_{d}", "bf16", 4, 2, d, 1500, [(60, 200), (700, 777)], [[(0, 333)], [(333, 617), (950, 27)], [(977, 523)]],
+                k_scale=2.0)
+    inputs = wl.make_inputs(w, 41)
+    ref = oracle_full(w, inputs)
+    plain = replay.ShardRun(w, inputs, DEV)
+    plain.step()
+    scaled_inputs = dict(inputs, d_o=inputs["d_o"] * 64)
+    assert torch.equal((scaled_inputs["d_o"].float() / 64).to(torch.bfloat16), inputs["d_o"])
+    big = replay.ShardRun(w, scaled_inputs, DEV)
+    big.step()
+    torch.cuda.synchronize()
+    for j in range(len(w.chunks)):
+        assert torch.equal(big.dk[j], plain.dk[j] * 64) and torch.equal(big.dv[j], plain.dv[j] * 64)
+    assert torch.equal(big.o, plain.o) and torch.equal(big.lse, plain.lse)
+    e_plain, _ = check("dq", plain.dq.cpu(), ref["dq"], "bf16")
+    e_big, _ = check("dq with residuals everywhere", (big.dq / 64).cpu(), ref["dq"], "bf16")
+    frac = float((big.dq / 64 != plain.dq).float().mean())
+    print(f"    dq elements changed by the residual path: {100 * frac:.1f} %", flush=True)
+    assert frac > 0.5 and e_big <= e_plain
+
+
 def test_future_chunk_and_merge_outputs():
     dev = torch.device(DEV)
     w = _custom("future", "bf16", 2, 1, 128, 512, [(0, 128)], [[(256, 256)]])
