@@ -342,6 +342,23 @@ def test_backward_halves_and_dq_reproducible():
     assert e.value.code == hexi.HEXI_EINVAL
 
 
+def test_dkdv_reproducible_when_a_workgroup_sums_the_whole_group(force_run_len):
+    # whole-group head runs use plain stores and a fixed summation order: dk / dv are bit-identical between runs
+    # (runs that split a group add with floating-point atomics, whose order may vary)
+    w = wl.config(2, shrink=16)
+    inputs = wl.make_inputs(w)
+    run = replay.ShardRun(w, inputs, DEV)
+    run.forward()
+    force_run_len(w.n_q_heads // w.n_kv_heads)
+    run.backward(); torch.cuda.synchronize()
+    first = [(a.clone(), b.clone()) for a, b in zip(run.dk, run.dv)]
+    for a, b in zip(run.dk, run.dv):
+        a.fill_(float("nan")); b.fill_(float("nan"))
+    run.backward(); torch.cuda.synchronize()
+    for (a0, b0), a1, b1 in zip(first, run.dk, run.dv):
+        assert torch.equal(a0, a1) and torch.equal(b0, b1)
+
+
 def test_forward_is_deterministic():
     w = wl.config(3, shrink=32)
     inputs = wl.make_inputs(w)
