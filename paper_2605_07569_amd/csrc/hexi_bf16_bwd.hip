@@ -3,7 +3,8 @@
 //
 // The workgroup keeps its K and V rows in registers as MFMA operands and its dK / dV tiles in accumulators
 // while it sweeps the 64-row q tiles that can see the key tile.  Per q tile: S = Q K^T and dP = dO V^T (keys
-// across lanes, query rows in-lane), P = exp2(S*scale*log2e - LSE*log2e) from the saved global LSE,
+// across lanes, query rows in-lane), P = exp2(S*scale*log2e - LSE*log2e) from the saved global LSE (each tile's
+// LSE values are multiplied by -log2e in LDS once, not once per score),
 // dS = P (dP - Delta), dV += P^T dO and dK += dS^T Q (dO and Q fetched with transposed LDS reads).  dQ is
 // produced by a separate q-stationary kernel: adding it from here would need one fp32 atomic per dS K element
 // per key tile, and that atomic traffic saturates the L2 atomic units long before the MFMA pipes.
@@ -288,7 +289,7 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 const int x = 4 * rb + t;
-                float pv = fast_exp2(fmaf(s[x], scale_log2, -LOG2E * l4[t]));
+                float pv = fast_exp2(fmaf(s[x], scale_log2, l4[t]));
                 if (MASKED) pv = my_kpos > qpv[t] ? 0.f : pv;
                 p[x] = pv;
                 ds[x] = pv * (dp[x] - d4[t]);
@@ -314,6 +315,14 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
         fetch_tile(0);
         if (n_seq > 1) fetch_tile(1);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        // The vector phase uses the row constant -log2(e) * LSE: each tile's 64 LSE values are converted in
+        // place once they have landed (one multiply per tile instead of 16 per wavefront): tile 0 here, by the
+        // wavefront that fetched it; tile i + 1 by a wavefront of group 1 at the start of its vector phase of
+        // tile i, the slot before the first vector phase that reads it.
+        if (grp == 0 && wg4 == 0) {
+            sm.lse[0][lane] = sm.lse[0][lane] * -LOG2E;
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
         if (grp == 1) wg_barrier();
         auto enter_m = [&](int i) __attribute__((always_inline)) {
             if (grp == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -324,6 +333,7 @@ __global__ void __launch_bounds__(512) bwd_dkdv_bf16_kernel(const BwdArgs a, con
             if (grp == 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             wg_barrier();
             if (grp == 1 && i + 2 < n_seq) fetch_tile(i + 2);
+            if (grp == 1 && wg4 == 3 && i + 1 < n_seq) sm.lse[(i + 1) % NB][lane] = sm.lse[(i + 1) % NB][lane] * -LOG2E;
             if (proc_t < n_masked) v_phase(i % NB, i & 7, std::true_type{});
             else v_phase(i % NB, i & 7, std::false_type{});
             if (++proc_t == n_all) proc_t = 0;
